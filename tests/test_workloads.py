@@ -1,0 +1,83 @@
+"""The seeded input generators and the stored batch snapshots (CPU only)."""
+import os
+
+import numpy as np
+import pytest
+
+from oracle import make_batch_snapshots
+from oracle.counters import counter_update
+from workloads import batches, make_block_table, make_step_batch, trace_for_config
+from workloads.tensors import f32_to_storage_bits
+
+
+def test_storage_rounding_is_round_to_nearest_even():
+    import torch
+
+    rng = np.random.default_rng(0)
+    x = np.concatenate([rng.standard_normal(20000).astype(np.float32) * 10,
+                        np.float32([1.00390625, 1.01171875, -1.00390625, 0.0, 65504.0])])
+    for dtype, tdt in (("f16", torch.float16), ("bf16", torch.bfloat16)):
+        ours = f32_to_storage_bits(x, dtype)
+        ref = torch.from_numpy(x).to(tdt).view(torch.int16).numpy().view(np.uint16)
+        assert np.array_equal(ours, ref)
+
+
+def test_block_table_is_a_partial_permutation():
+    rng = np.random.default_rng(1)
+    seq = [1, 16, 17, 0, 300]
+    table, nb = make_block_table(rng, seq, 16, spare_blocks=5)
+    need = [(s + 15) // 16 for s in seq]
+    used = np.concatenate([table[r, :n] for r, n in enumerate(need)])
+    assert len(set(used.tolist())) == len(used) == sum(need)
+    assert used.min() >= 0 and used.max() < nb and nb == sum(need) + 5
+    assert table.shape[1] == max(need)
+
+
+@pytest.mark.parametrize("cfg", [1, 2, 3, 4, 5])
+def test_step_batches_have_the_stated_shapes(cfg):
+    b = make_step_batch(cfg)
+    n = {1: 8, 2: 64, 3: 256, 4: 512, 5: 256}[cfg]
+    assert b.num_decode == n and b.client_ids.shape == (n,)
+    assert b.num_clients == {1: 2, 2: 2, 3: 4, 4: 27, 5: 8}[cfg]
+    assert b.client_ids.min() >= 0 and b.client_ids.max() < b.num_clients
+    assert (b.w_p, b.w_q) == (1, 2)
+    assert b.shape.dtype == ("f16" if cfg <= 3 else "bf16")
+    assert b.shape.num_kv_heads == (32 if cfg <= 3 else 8)
+    lo, hi = {1: (16, 256), 2: (256, 640), 3: (65, 2048 + 512), 4: (3, 8192), 5: (128, 4096)}[cfg]
+    assert b.seq_lens.min() >= lo and b.seq_lens.max() <= hi
+    assert b.decode_kv_bytes == int(b.seq_lens.sum()) * b.shape.kv_bytes_per_token
+    if cfg == 5:
+        assert b.num_prefill == 16 and b.prefill_causal_pairs == 16 * (256 * 257 // 2)
+        b1 = make_step_batch(5, prefill_chunk=1)
+        assert b1.prefill_causal_pairs == 16 * (256 * 256 + 256 * 257 // 2)
+        assert np.array_equal(b1.seq_lens, b.seq_lens)
+        ids, n_in, n_out = b.counter_update_args(first_chunk=True)
+        assert len(ids) == 272 and n_in.sum() == 16 * 512 and n_out.sum() == 256
+        assert b1.counter_update_args(first_chunk=False)[1].sum() == 0
+
+
+@pytest.mark.parametrize("cfg", [3, 4])
+def test_snapshots_are_what_the_scheduler_script_writes(cfg, tmp_path, monkeypatch):
+    stored = open(os.path.join(batches.DATA_DIR, f"cfg{cfg}_batch.txt"), encoding="ascii").read()
+    monkeypatch.setattr(make_batch_snapshots, "DATA_DIR", str(tmp_path))
+    path = make_batch_snapshots.write(cfg)
+    assert open(path, encoding="ascii").read() == stored
+
+
+@pytest.mark.parametrize("cfg", [3, 4])
+def test_snapshot_is_self_consistent(cfg):
+    b = make_step_batch(cfg)
+    trace, p = trace_for_config(cfg)
+    by_rid = {r.rid: r for r in trace}
+    path = os.path.join(batches.DATA_DIR, f"cfg{cfg}_batch.txt")
+    rows = [list(map(int, ln.split())) for ln in open(path) if ln.strip() and not ln.startswith("#")]
+    assert len(rows) == p["max_batch"] == b.num_decode
+    for rid, cl, n_in, gen, s in rows:
+        r = by_rid[rid]
+        assert (r.client, r.n_input) == (cl, n_in)
+        assert 0 <= gen < r.n_output and s == n_in + gen + 1
+    # the recorded counters differ by exactly the decode charge of Algorithm 2
+    ids, n_in, n_out = b.counter_update_args()
+    assert counter_update(b.counters_before, ids, n_in, n_out, b.w_p, b.w_q) == b.counters_after.tolist()
+    # VTC keeps the overloaded clients' counters close together
+    assert b.counters_before.max() - b.counters_before.min() < 2 * p["w_q"] * p["M"]
