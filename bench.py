@@ -1,0 +1,230 @@
+#!/usr/bin/env python3
+"""Benchmark of one VTC serving step on one MI355X.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload cfg3|cfg4|cfg5] [--no-cpu-baseline]
+
+A step is one pass of the hot path over one synthetic batch that is already
+resident in HBM: decode attention over the paged KV cache of every running
+request, the prefill-chunk attention of newly admitted prompts when the
+workload has any (cfg5), and one virtual-token-counter update for the whole
+batch.  Prints ONE JSON line: whole-step KV GB/s as ``value``, plus the
+roofline of the dominant kernel (decode attention, HBM-bound; its duration is
+measured with HIP events recorded on the launch stream right around that
+kernel) and the CPU oracle timed on a bounded sample of the same workload.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import math
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0          # MI355X HBM3E, published
+MFMA_PEAK_TFLOPS = 2500.0      # dense bf16 / fp16
+
+
+def parse_args():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=50)
+    ap.add_argument("--warmup", type=int, default=10)
+    ap.add_argument("--workload", default="cfg3", choices=["cfg2", "cfg3", "cfg4", "cfg5"])
+    ap.add_argument("--prefill-chunk", type=int, default=1, choices=[0, 1], help="cfg5: which 256-token chunk")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--cpu-sample-requests", type=int, default=12)
+    return ap.parse_args()
+
+
+def cpu_baseline(st, scale, sample_requests):
+    """Time the fp64 oracle on a bounded sample of the decode batch, on the host cores."""
+    import numpy as np
+    from concurrent.futures import ThreadPoolExecutor
+
+    from oracle import attention as OA          # the only use of the oracle here: the reported CPU baseline
+    from workloads import tensor_to_bits
+
+    try:
+        from threadpoolctl import threadpool_limits
+    except Exception:                            # pragma: no cover
+        threadpool_limits = None
+    b = st.batch
+    sh = b.shape
+    rng = np.random.default_rng(7)
+    picks = sorted(int(x) for x in rng.choice(b.num_decode, size=min(sample_requests, b.num_decode), replace=False))
+    # compact copy of the sampled requests' blocks (host), with a remapped block table
+    bs = sh.block_size
+    tables, blocks, at = [], [], 0
+    width = max((int(b.seq_lens[r]) + bs - 1) // bs for r in picks)
+    for r in picks:
+        nb = (int(b.seq_lens[r]) + bs - 1) // bs
+        blocks.append(st.block_table[r, :nb].long())
+        row = np.zeros(width, dtype=np.int32)
+        row[:nb] = np.arange(at, at + nb)
+        tables.append(row)
+        at += nb
+    import torch
+
+    idx = torch.cat(blocks)
+    k_bits = tensor_to_bits(st.k_cache[idx])
+    v_bits = tensor_to_bits(st.v_cache[idx])
+    q_bits = tensor_to_bits(st.q[torch.as_tensor(picks, device=st.q.device)])
+    table = np.stack(tables)
+    seq = [int(b.seq_lens[r]) for r in picks]
+    cores = max(1, min(16, os.cpu_count() or 1, len(picks)))
+
+    def one(i):
+        return OA.paged_decode(q_bits[i:i + 1], k_bits, v_bits, table[i:i + 1], seq[i:i + 1], scale, sh.dtype)
+
+    def run():
+        t0 = time.perf_counter()
+        with ThreadPoolExecutor(max_workers=cores) as pool:
+            list(pool.map(one, range(len(picks))))
+        return time.perf_counter() - t0
+
+    if threadpool_limits is not None:
+        with threadpool_limits(limits=1):
+            secs = run()
+    else:
+        secs = run()
+    kv_bytes = sum(seq) * sh.kv_bytes_per_token
+    return {
+        "value": kv_bytes / secs / 1e9,
+        "unit": "GB/s",
+        "cores": cores,
+        "kind": "oracle",
+        "sample": f"{len(picks)} of {b.num_decode} decode requests x all {sh.num_q_heads} q heads "
+                  f"({sum(seq)} context tokens, {kv_bytes / 1e6:.1f} MB of KV), fp64 numpy, {secs:.2f} s",
+        "seconds": secs,
+    }
+
+
+def main() -> int:
+    args = parse_args()
+    if args.gpus != 1:
+        print(f"bench.py: this build runs on one GPU only (got --gpus {args.gpus}); "
+              "the serving step has no multi-GPU path.", file=sys.stderr)
+        return 2
+
+    import torch
+
+    import paper_2401_00588_amd as vtc
+    from workloads import make_device_step, make_step_batch
+
+    vtc.load_library()                           # fail loudly if the HIP extension is missing
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible", file=sys.stderr)
+        return 2
+    torch.cuda.set_device(0)
+    cfg = int(args.workload[3:])
+    batch = make_step_batch(cfg, prefill_chunk=args.prefill_chunk) if cfg == 5 else make_step_batch(cfg)
+    st = make_device_step(batch)
+    sh = batch.shape
+    scale = 1.0 / math.sqrt(sh.head_dim)
+    params = vtc.make_params(sh.num_q_heads, sh.num_kv_heads, sh.head_dim, sh.block_size, st.max_blocks_per_seq,
+                             sh.dtype, scale)
+    ws = torch.empty(vtc.vtc_attn_workspace_bytes(params, batch.num_decode, 0), dtype=torch.uint8, device="cuda")
+    out = torch.empty_like(st.q)
+    pf_out = torch.empty_like(st.pf_q) if batch.num_prefill else None
+    stream = torch.cuda.Stream()
+
+    def step(ev_b=None, ev_e=None, pf_ev=None):
+        if batch.num_prefill:
+            if pf_ev is not None:
+                pf_ev[0].record(stream)
+            vtc.vtc_attn_prefill_chunk(params, st.pf_q, st.pf_cu_q_lens, st.pf_max_q_len, st.k_cache, st.v_cache,
+                                       st.pf_block_table, st.pf_seq_lens, out=pf_out)
+            if pf_ev is not None:
+                pf_ev[1].record(stream)
+        vtc.vtc_attn_decode(params, st.q, st.k_cache, st.v_cache, st.block_table, st.seq_lens, out=out,
+                            workspace=ws, ev_begin=ev_b, ev_end=ev_e)
+        vtc.vtc_counter_update(st.counters, st.cu_client_ids, st.cu_n_in, st.cu_n_out, batch.w_p, batch.w_q)
+
+    begins = [vtc.HipEvent() for _ in range(args.steps)]
+    ends = [vtc.HipEvent() for _ in range(args.steps)]
+    pf_events = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True))
+                 for _ in range(args.steps)] if batch.num_prefill else None
+    with torch.cuda.stream(stream):
+        for _ in range(args.warmup):
+            step()
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for i in range(args.steps):
+            step(begins[i], ends[i], pf_events[i] if pf_events else None)
+        torch.cuda.synchronize()
+        t1 = time.perf_counter()
+    ms_per_step = (t1 - t0) * 1e3 / args.steps
+    kernel_ms = sorted(b.elapsed_ms(e) for b, e in zip(begins, ends))
+    kernel_avg_ms = sum(kernel_ms) / len(kernel_ms)
+
+    kv_bytes = batch.decode_kv_bytes
+    value = kv_bytes / (ms_per_step * 1e-3) / 1e9
+    achieved = kv_bytes / (kernel_avg_ms * 1e-3) / 1e9
+    line = {
+        "metric": "decode attention KV GB/s over one VTC serving step (1 GPU)",
+        "value": round(value, 2),
+        "unit": "GB/s",
+        "n_gpus": 1,
+        "steps": args.steps,
+        "warmup": args.warmup,
+        "ms_per_step": round(ms_per_step, 5),
+        "higher_is_better": True,
+        "scaling": "weak",
+        "vs_baseline": None,
+        "dtype": sh.dtype,
+        "data": "synthetic",
+        "config": {
+            "workload": {2: "cfg2: 64-request Llama-2-7B-shaped decode", 3: "cfg3: 4-client mixed decode, 256 requests, "
+                         "MHA 32 heads, head_dim 128, fp16, block 16, batch admitted by the CPU VTC scheduler",
+                         4: "cfg4: 27-client GQA 32/8 bf16 decode, 512 requests",
+                         5: f"cfg5: mixed step, 16 prompts x 256-token prefill chunk {args.prefill_chunk} + 256 decodes, GQA 32/8 bf16"}[cfg],
+            "requests": batch.num_decode,
+            "context_tokens": int(batch.seq_lens.sum()),
+            "kv_bytes": kv_bytes,
+            "clients": batch.num_clients,
+            "prefill_tokens": int(batch.pf_q_lens.sum()) if batch.num_prefill else 0,
+        },
+        "pct_of_hbm_peak": round(100.0 * value / HBM_PEAK_GBS, 2),
+        "tokens_per_s": round(batch.tokens_advanced / (ms_per_step * 1e-3), 1),
+        "roofline": {
+            "kernel": "decode_attend_kernel",
+            "bound": "hbm",
+            "achieved": round(achieved, 2),
+            "peak": HBM_PEAK_GBS,
+            "unit": "GB/s",
+            "frac": round(achieved / HBM_PEAK_GBS, 4),
+            "traffic": None,
+            "kernel_avg_ms": round(kernel_avg_ms, 5),
+            "kernel_min_ms": round(kernel_ms[0], 5),
+            "kernel_median_ms": round(kernel_ms[len(kernel_ms) // 2], 5),
+            "algorithmic_bytes_per_launch": kv_bytes,
+        },
+    }
+    if pf_events:
+        pf_ms = sorted(a.elapsed_time(b) for a, b in pf_events)
+        pf_avg = sum(pf_ms) / len(pf_ms)
+        line["prefill"] = {
+            "kernel": "prefill_chunk_kernel",
+            "bound": "mfma",
+            "flops": batch.prefill_flops,
+            "avg_ms": round(pf_avg, 5),
+            "achieved": round(batch.prefill_flops / (pf_avg * 1e-3) / 1e12, 2),
+            "peak": MFMA_PEAK_TFLOPS,
+            "unit": "TFLOP/s",
+            "frac": round(batch.prefill_flops / (pf_avg * 1e-3) / 1e12 / MFMA_PEAK_TFLOPS, 4),
+        }
+    if not args.no_cpu_baseline:
+        line["cpu_baseline"] = cpu_baseline(st, scale, args.cpu_sample_requests)
+        line["cpu_baseline"]["value"] = round(line["cpu_baseline"]["value"], 4)
+        line["cpu_baseline"]["seconds"] = round(line["cpu_baseline"]["seconds"], 3)
+    print(json.dumps(line), flush=True)
+    return 0
+
+
+if __name__ == "__main__":
+    sys.exit(main())

@@ -1,0 +1,195 @@
+/*
+ * vtc.h -- C ABI of the MI355X (gfx950) hot path of one Virtual Token Counter
+ * serving step: paged-KV decode attention, causal prefill-chunk attention and
+ * the per-client virtual-token-counter charge.
+ *
+ * Paper: "Fairness in Serving Large Language Models" (arXiv 2401.00588).
+ * One iteration of the execution stream of Algorithm 2 calls
+ *     forward_prefill(B_new)  ->  vtc_attn_prefill_chunk   (attention part)
+ *     forward_decode(B)       ->  vtc_attn_decode          (attention part)
+ *     c_i += ...              ->  vtc_counter_update
+ * The paper names a paged KV cache as its substrate (Section 5.1) and gives no
+ * attention formula; the kernels compute standard scaled dot-product softmax
+ * attention (see each entry point).
+ *
+ * Conventions
+ *   - Every pointer marked [device] is a device pointer valid on the current
+ *     HIP device; [host] pointers are ordinary host memory.
+ *   - The caller owns every buffer (including workspace and counters).  The
+ *     library allocates no device memory and never frees caller memory.
+ *   - Calls enqueue work on `hip_stream` (a hipStream_t passed as void*, NULL
+ *     is the default stream) and return without synchronising; results are
+ *     valid once the caller has synchronised that stream.
+ *   - Return value: VTC_OK (0) or a negative VTC_ERR_* code.  Arguments that
+ *     are visible on the host are validated before any HIP call is made, so
+ *     every error path below can be exercised on a machine without a GPU.
+ *     Device-resident contents (seq_lens, block_table, client_ids, ...) are
+ *     trusted, except where a clamp is documented.
+ *
+ * Layouts (row-major, last index fastest; E = 2-byte element, fp16 or bf16)
+ *   q, out        E [num_q_tokens, num_q_heads, head_dim]
+ *   k_cache,
+ *   v_cache       E [num_blocks, num_kv_heads, block_size, head_dim]
+ *   block_table   int32 [num_seqs, max_blocks_per_seq]   physical block ids
+ *   seq_lens      int32 [num_seqs]
+ * Token p of sequence r lives in block block_table[r][p / block_size], row
+ * p % block_size.  Query head h reads KV head h / (num_q_heads/num_kv_heads).
+ */
+#ifndef VTC_H_
+#define VTC_H_
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum { VTC_F16 = 0, VTC_BF16 = 1 } vtc_dtype;
+
+enum {
+  VTC_OK = 0,
+  VTC_ERR_INVALID_ARG = -1,         /* null pointer, negative size, inconsistent sizes   */
+  VTC_ERR_UNSUPPORTED = -2,         /* head_dim != 128, block_size != 16, unknown dtype,
+                                       num_q_heads/num_kv_heads not in {1,2,4,8}          */
+  VTC_ERR_WORKSPACE_TOO_SMALL = -3, /* workspace_bytes < vtc_attn_workspace_bytes(...)   */
+  VTC_ERR_HIP = -4                  /* a HIP runtime call or kernel launch failed        */
+};
+
+/* Host struct, passed by const pointer; never retained by the library. */
+typedef struct {
+  int32_t num_q_heads;        /* Hq                                              */
+  int32_t num_kv_heads;       /* Hkv, must divide Hq                             */
+  int32_t head_dim;           /* 128                                             */
+  int32_t block_size;         /* tokens per KV block: 16                         */
+  int32_t max_blocks_per_seq; /* row stride of block_table                       */
+  int32_t dtype;              /* vtc_dtype of q, k_cache, v_cache and out        */
+  float scale;                /* logit scale, normally 1/sqrt(head_dim)          */
+} vtc_attn_params;
+
+/*
+ * Bytes of device workspace that vtc_attn_decode needs for up to max_num_seqs
+ * sequences of up to max_seq_len context tokens each (max_seq_len <= 0, or
+ * larger than the block table can address, means max_blocks_per_seq *
+ * block_size).  Pure host arithmetic.  Returns 0 if params is NULL or
+ * unsupported.  vtc_attn_prefill_chunk needs no workspace.
+ */
+size_t vtc_attn_workspace_bytes(const vtc_attn_params* params /*[host]*/, int32_t max_num_seqs,
+                                int32_t max_seq_len);
+
+/*
+ * Decode attention -- the attention part of forward_decode(B) in Algorithm 2
+ * (one new token per running request, Section 2.1 "decoding").
+ *
+ * For each sequence r < num_seqs and query head h:
+ *     out[r,h,:] = sum_j softmax_j(scale * <q[r,h,:], K_j>) * V_j,  j in [0, seq_lens[r])
+ * over the cached tokens of KV head h / (Hq/Hkv).  The K/V of the current
+ * token must already be in the cache (seq_lens includes it).  Accumulation is
+ * fp32; out is rounded to the storage dtype (nearest even).  seq_lens[r] == 0
+ * gives an all-zero row.  seq_lens[r] is clamped to max_blocks_per_seq *
+ * block_size.  Rows of the last block past seq_lens[r], and block_table
+ * entries past the last block, are never used (they may hold anything).
+ *
+ *   q [device]          E [num_seqs, Hq, 128]
+ *   k_cache, v_cache    [device] paged caches, read only
+ *   block_table         [device] int32 [num_seqs, max_blocks_per_seq]
+ *   seq_lens            [device] int32 [num_seqs]
+ *   out [device]        E [num_seqs, Hq, 128], written
+ *   workspace [device]  >= vtc_attn_workspace_bytes(params, num_seqs, 0) bytes,
+ *                       256-byte aligned, contents undefined before and after
+ * num_seqs == 0 is a successful no-op.  The call enqueues a planning kernel, the
+ * attention kernel and a merge kernel on hip_stream; two calls that share one
+ * workspace must be ordered on the same stream.
+ */
+int vtc_attn_decode(const vtc_attn_params* params /*[host]*/, int32_t num_seqs, const void* q,
+                    const void* k_cache, const void* v_cache, const int32_t* block_table,
+                    const int32_t* seq_lens, void* out, void* workspace, size_t workspace_bytes,
+                    void* hip_stream);
+
+/*
+ * Measurement hook: exactly vtc_attn_decode, and in addition records the HIP
+ * events ev_begin / ev_end (hipEvent_t passed as void*, created by the caller
+ * with timing enabled) on hip_stream immediately before and after the attention
+ * kernel proper, i.e. excluding the planning and merge kernels.  Either event
+ * may be NULL.  Used by the benchmark to time the HBM-bound kernel of the decode
+ * step (Algorithm 2, forward_decode) by itself.
+ */
+int vtc_attn_decode_profiled(const vtc_attn_params* params /*[host]*/, int32_t num_seqs, const void* q,
+                             const void* k_cache, const void* v_cache, const int32_t* block_table,
+                             const int32_t* seq_lens, void* out, void* workspace,
+                             size_t workspace_bytes, void* hip_stream, void* ev_begin, void* ev_end);
+
+/*
+ * Causal prefill-chunk attention -- the attention part of forward_prefill(B_new)
+ * in Algorithm 2 (Section 2.1 "prefilling"), for one chunk of each newly
+ * admitted prompt.  Chunking is this library's batching unit; the paper
+ * prefills whole prompts, which is the single-chunk case.
+ *
+ * Sequence r contributes Lq_r = cu_q_lens[r+1] - cu_q_lens[r] query tokens,
+ * stored at rows cu_q_lens[r] .. cu_q_lens[r+1]-1 of q and out.  seq_lens[r]
+ * is its context length AFTER the chunk's K/V were appended to the cache, so
+ * chunk token i sits at absolute position p = seq_lens[r] - Lq_r + i and
+ * attends to cached tokens 0..p inclusive:
+ *     out[row,h,:] = sum_{j<=p} softmax_j(scale * <q[row,h,:], K_j>) * V_j
+ * fp32 accumulation, output rounded to the storage dtype.  Softmax weights are
+ * rounded to the storage dtype before the P*V product (matrix-core operand).
+ *
+ *   q [device]          E [total_q_tokens, Hq, 128], total_q_tokens = cu_q_lens[num_seqs]
+ *   cu_q_lens [device]  int32 [num_seqs + 1], non-decreasing, cu_q_lens[0] == 0
+ *   max_q_len           host-side upper bound on every Lq_r (sizes the launch)
+ *   seq_lens [device]   int32 [num_seqs], seq_lens[r] >= Lq_r
+ *   out [device]        E [total_q_tokens, Hq, 128], written
+ *   workspace           unused, may be NULL
+ * num_seqs == 0 or max_q_len == 0 is a successful no-op.
+ */
+int vtc_attn_prefill_chunk(const vtc_attn_params* params /*[host]*/, int32_t num_seqs,
+                           const void* q, const int32_t* cu_q_lens, int32_t max_q_len,
+                           const void* k_cache, const void* v_cache, const int32_t* block_table,
+                           const int32_t* seq_lens, void* out, void* workspace,
+                           size_t workspace_bytes, void* hip_stream);
+
+/*
+ * Virtual-token-counter charge (Algorithm 2: admission charge
+ * c_k += w_p * input_length(r), and decode charge
+ * c_i += w_q * |{r in B : client(r) = i}|; Algorithm 4 states both as "when new
+ * tokens have been processed" with the weighted-token cost of Section 3.1):
+ *     counters[client_ids[r]] += w_p * n_input_tokens[r] + w_q * n_output_tokens[r]
+ * for every r < n, as exact two's-complement int64 arithmetic (the result does
+ * not depend on the order of summation).  Either token array may be NULL,
+ * meaning all zero.  Requests whose client id is outside [0, num_clients) are
+ * ignored.  Token counts may be negative (a refund).
+ *
+ *   counters [device]         int64 [num_clients], updated in place
+ *   client_ids [device]       int32 [n]
+ *   n_input_tokens [device]   int32 [n] or NULL
+ *   n_output_tokens [device]  int32 [n] or NULL
+ * n == 0 is a successful no-op.
+ */
+int vtc_counter_update(int64_t* counters, int32_t num_clients, const int32_t* client_ids,
+                       const int32_t* n_input_tokens, const int32_t* n_output_tokens, int32_t n,
+                       int64_t w_p, int64_t w_q, void* hip_stream);
+
+/*
+ * Test hook for the paged-cache index arithmetic: writes, for every sequence r
+ * and position p < seq_lens[r], the physical slot
+ *     slot(r,p) = block_table[r][p / block_size] * block_size + p % block_size
+ * to slots_out[cu_out[r] + p].  cu_out [device] int32 [num_seqs+1] are the
+ * exclusive prefix sums of seq_lens; max_seq_len is a host-side upper bound on
+ * seq_lens (sizes the launch).  Uses the same index helper as the attention
+ * kernels.
+ */
+int vtc_debug_gather_slots(const vtc_attn_params* params /*[host]*/, int32_t num_seqs,
+                           const int32_t* block_table, const int32_t* seq_lens,
+                           const int32_t* cu_out, int32_t max_seq_len, int32_t* slots_out,
+                           void* hip_stream);
+
+/* Static, NUL-terminated description of a return code.  Never NULL. */
+const char* vtc_strerror(int code);
+
+/* Library version as major*10000 + minor*100 + patch. */
+int vtc_version(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* VTC_H_ */

@@ -1,0 +1,115 @@
+// C ABI entry points: host-side validation, then the kernel launchers.
+// Every check on host-visible arguments runs before the first HIP call.
+#include "vtc_internal.h"
+
+#include <mutex>
+
+namespace vtc {
+
+int device_cu_count() {
+  static std::mutex mu;
+  static int cached[64];
+  int dev = 0;
+  if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64) return 256;
+  std::lock_guard<std::mutex> lock(mu);
+  if (cached[dev] == 0) {
+    int n = 0;
+    if (hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || n <= 0) n = 256;
+    cached[dev] = n;
+  }
+  return cached[dev];
+}
+
+}  // namespace vtc
+
+extern "C" {
+
+int vtc_version(void) { return 100; }
+
+const char* vtc_strerror(int code) {
+  switch (code) {
+    case VTC_OK: return "success";
+    case VTC_ERR_INVALID_ARG: return "invalid argument (null pointer, negative or inconsistent size)";
+    case VTC_ERR_UNSUPPORTED:
+      return "unsupported configuration (need head_dim 128, block_size 16, fp16/bf16, "
+             "num_q_heads/num_kv_heads in {1,2,4,8})";
+    case VTC_ERR_WORKSPACE_TOO_SMALL: return "workspace smaller than vtc_attn_workspace_bytes()";
+    case VTC_ERR_HIP: return "HIP runtime error (launch failed or no usable device)";
+    default: return "unknown error code";
+  }
+}
+
+size_t vtc_attn_workspace_bytes(const vtc_attn_params* params, int32_t max_num_seqs, int32_t max_seq_len) {
+  if (vtc::check_params(params) != VTC_OK || max_num_seqs < 0) return 0;
+  return vtc::decode_workspace_layout(*params, max_num_seqs, max_seq_len).total_bytes;
+}
+
+int vtc_attn_decode_profiled(const vtc_attn_params* params, int32_t num_seqs, const void* q, const void* k_cache,
+                             const void* v_cache, const int32_t* block_table, const int32_t* seq_lens, void* out,
+                             void* workspace, size_t workspace_bytes, void* hip_stream, void* ev_begin,
+                             void* ev_end) {
+  int rc = vtc::check_params(params);
+  if (rc != VTC_OK) return rc;
+  if (num_seqs < 0) return VTC_ERR_INVALID_ARG;
+  if (num_seqs == 0) return VTC_OK;
+  if (!q || !k_cache || !v_cache || !block_table || !seq_lens || !out || !workspace) return VTC_ERR_INVALID_ARG;
+  if ((reinterpret_cast<uintptr_t>(workspace) & 255u) != 0) return VTC_ERR_INVALID_ARG;
+  if ((reinterpret_cast<uintptr_t>(q) & 15u) || (reinterpret_cast<uintptr_t>(out) & 15u) ||
+      (reinterpret_cast<uintptr_t>(k_cache) & 15u) || (reinterpret_cast<uintptr_t>(v_cache) & 15u))
+    return VTC_ERR_INVALID_ARG;
+  if (workspace_bytes < vtc::decode_workspace_layout(*params, num_seqs, 0).total_bytes)
+    return VTC_ERR_WORKSPACE_TOO_SMALL;
+  return vtc::launch_decode(*params, num_seqs, q, k_cache, v_cache, block_table, seq_lens, out, workspace,
+                            static_cast<hipStream_t>(hip_stream), static_cast<hipEvent_t>(ev_begin),
+                            static_cast<hipEvent_t>(ev_end));
+}
+
+int vtc_attn_decode(const vtc_attn_params* params, int32_t num_seqs, const void* q, const void* k_cache,
+                    const void* v_cache, const int32_t* block_table, const int32_t* seq_lens, void* out,
+                    void* workspace, size_t workspace_bytes, void* hip_stream) {
+  return vtc_attn_decode_profiled(params, num_seqs, q, k_cache, v_cache, block_table, seq_lens, out, workspace,
+                                  workspace_bytes, hip_stream, nullptr, nullptr);
+}
+
+int vtc_attn_prefill_chunk(const vtc_attn_params* params, int32_t num_seqs, const void* q,
+                           const int32_t* cu_q_lens, int32_t max_q_len, const void* k_cache,
+                           const void* v_cache, const int32_t* block_table, const int32_t* seq_lens,
+                           void* out, void* workspace, size_t workspace_bytes, void* hip_stream) {
+  (void)workspace;
+  (void)workspace_bytes;
+  int rc = vtc::check_params(params);
+  if (rc != VTC_OK) return rc;
+  if (num_seqs < 0 || max_q_len < 0) return VTC_ERR_INVALID_ARG;
+  if (num_seqs == 0 || max_q_len == 0) return VTC_OK;
+  if (!q || !cu_q_lens || !k_cache || !v_cache || !block_table || !seq_lens || !out) return VTC_ERR_INVALID_ARG;
+  if ((reinterpret_cast<uintptr_t>(q) & 15u) || (reinterpret_cast<uintptr_t>(out) & 15u) ||
+      (reinterpret_cast<uintptr_t>(k_cache) & 15u) || (reinterpret_cast<uintptr_t>(v_cache) & 15u))
+    return VTC_ERR_INVALID_ARG;
+  return vtc::launch_prefill(*params, num_seqs, q, cu_q_lens, max_q_len, k_cache, v_cache, block_table,
+                             seq_lens, out, static_cast<hipStream_t>(hip_stream));
+}
+
+int vtc_counter_update(int64_t* counters, int32_t num_clients, const int32_t* client_ids,
+                       const int32_t* n_input_tokens, const int32_t* n_output_tokens, int32_t n, int64_t w_p,
+                       int64_t w_q, void* hip_stream) {
+  if (n < 0 || num_clients < 0) return VTC_ERR_INVALID_ARG;
+  if (n == 0) return VTC_OK;
+  if (num_clients == 0) return VTC_OK;   // every id is out of range: nothing to charge
+  if (!counters || !client_ids) return VTC_ERR_INVALID_ARG;
+  return vtc::launch_counter_update(counters, num_clients, client_ids, n_input_tokens, n_output_tokens, n, w_p,
+                                    w_q, static_cast<hipStream_t>(hip_stream));
+}
+
+int vtc_debug_gather_slots(const vtc_attn_params* params, int32_t num_seqs, const int32_t* block_table,
+                           const int32_t* seq_lens, const int32_t* cu_out, int32_t max_seq_len,
+                           int32_t* slots_out, void* hip_stream) {
+  int rc = vtc::check_params(params);
+  if (rc != VTC_OK) return rc;
+  if (num_seqs < 0 || max_seq_len < 0) return VTC_ERR_INVALID_ARG;
+  if (num_seqs == 0 || max_seq_len == 0) return VTC_OK;
+  if (!block_table || !seq_lens || !cu_out || !slots_out) return VTC_ERR_INVALID_ARG;
+  return vtc::launch_gather_slots(*params, num_seqs, block_table, seq_lens, cu_out, max_seq_len, slots_out,
+                                  static_cast<hipStream_t>(hip_stream));
+}
+
+}  // extern "C"

@@ -1,0 +1,161 @@
+// Internal helpers shared by the gfx950 kernels of the VTC serving step.
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stddef.h>
+#include <stdint.h>
+
+#include "vtc.h"
+
+namespace vtc {
+
+constexpr int kHeadDim = 128;       // the only supported head_dim
+constexpr int kBlockSize = 16;      // tokens per KV block
+constexpr int kWave = 64;           // CDNA wavefront
+constexpr int kTileElems = kBlockSize * kHeadDim;   // elements of one (block, kv head) K or V tile
+constexpr float kLog2e = 1.4426950408889634f;
+
+// Split of a context into work items for decode attention: each item covers
+// kChunkTokens consecutive tokens of one (sequence, kv head).
+constexpr int kChunkTokens = 256;
+constexpr int kChunkBlocks = kChunkTokens / kBlockSize;
+
+// One fp32 partial result of a chunk: running max m (log2 domain), sum l, acc[128].
+constexpr int kPartialFloats = kHeadDim;
+
+using u32x4 = uint32_t __attribute__((ext_vector_type(4)));
+using f16x2 = _Float16 __attribute__((ext_vector_type(2)));
+using bf16x2 = __bf16 __attribute__((ext_vector_type(2)));
+
+struct F16 {};
+struct BF16 {};
+
+// Physical slot of token p of a sequence whose block-table row is `row`.
+// Paged KV cache (Section 5.1 of the paper names it; this is the usual index).
+__device__ __forceinline__ int32_t slot_of(const int32_t* __restrict__ row, int32_t p) {
+  return row[p / kBlockSize] * kBlockSize + p % kBlockSize;
+}
+
+// ---- 16-bit element helpers -------------------------------------------------
+template <typename T>
+__device__ __forceinline__ float dot2(uint32_t a, uint32_t b, float c);
+template <>
+__device__ __forceinline__ float dot2<F16>(uint32_t a, uint32_t b, float c) {
+  return __builtin_amdgcn_fdot2(__builtin_bit_cast(f16x2, a), __builtin_bit_cast(f16x2, b), c, false);
+}
+template <>
+__device__ __forceinline__ float dot2<BF16>(uint32_t a, uint32_t b, float c) {
+  return __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2, a), __builtin_bit_cast(bf16x2, b), c, false);
+}
+
+template <typename T>
+__device__ __forceinline__ float lo_f32(uint32_t w);
+template <typename T>
+__device__ __forceinline__ float hi_f32(uint32_t w);
+template <>
+__device__ __forceinline__ float lo_f32<F16>(uint32_t w) {
+  return (float)__builtin_bit_cast(f16x2, w)[0];
+}
+template <>
+__device__ __forceinline__ float hi_f32<F16>(uint32_t w) {
+  return (float)__builtin_bit_cast(f16x2, w)[1];
+}
+template <>
+__device__ __forceinline__ float lo_f32<BF16>(uint32_t w) {
+  return __builtin_bit_cast(float, w << 16);
+}
+template <>
+__device__ __forceinline__ float hi_f32<BF16>(uint32_t w) {
+  return __builtin_bit_cast(float, w & 0xffff0000u);
+}
+
+// Round two floats to the storage type (nearest even) and pack them.
+template <typename T>
+__device__ __forceinline__ uint32_t pack2(float a, float b);
+template <>
+__device__ __forceinline__ uint32_t pack2<F16>(float a, float b) {
+  f16x2 v = {(_Float16)a, (_Float16)b};
+  return __builtin_bit_cast(uint32_t, v);
+}
+__device__ __forceinline__ uint32_t bf16_bits(float x) {
+  uint32_t u = __builtin_bit_cast(uint32_t, x);
+  if ((u & 0x7fffffffu) > 0x7f800000u) return (u >> 16) | 0x40u;   // keep NaN a NaN
+  return (u + 0x7fffu + ((u >> 16) & 1u)) >> 16;
+}
+template <>
+__device__ __forceinline__ uint32_t pack2<BF16>(float a, float b) {
+  return bf16_bits(a) | (bf16_bits(b) << 16);
+}
+
+// ---- cross-lane helpers -----------------------------------------------------
+// Sum over the 16 lanes of a DPP row; every lane of the row gets the total.
+__device__ __forceinline__ float row16_allreduce_sum(float x) {
+  x += __builtin_amdgcn_update_dpp(0.f, x, 0xB1, 0xf, 0xf, false);    // quad_perm [1,0,3,2]
+  x += __builtin_amdgcn_update_dpp(0.f, x, 0x4E, 0xf, 0xf, false);    // quad_perm [2,3,0,1]
+  x += __builtin_amdgcn_update_dpp(0.f, x, 0x141, 0xf, 0xf, false);   // row_half_mirror
+  x += __builtin_amdgcn_update_dpp(0.f, x, 0x140, 0xf, 0xf, false);   // row_mirror
+  return x;
+}
+
+__device__ __forceinline__ float fast_exp2(float x) { return __builtin_amdgcn_exp2f(x); }
+
+// ---- host side --------------------------------------------------------------
+struct DecodeWorkspace {
+  size_t chunk_start_off;   // int32 [num_seqs + 1]   exclusive prefix of chunks per sequence
+  size_t items_off;         // int2  [max_items]      (sequence, chunk index)
+  size_t ml_off;            // float2[max_items * Hq] (m, l) per partial
+  size_t acc_off;           // float [max_items * Hq * 128]
+  size_t total_bytes;
+  int64_t max_items;
+};
+
+inline size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
+
+inline DecodeWorkspace decode_workspace_layout(const vtc_attn_params& p, int32_t num_seqs, int32_t max_seq_len) {
+  const int64_t cap = (int64_t)p.max_blocks_per_seq * p.block_size;
+  int64_t s = (max_seq_len <= 0 || max_seq_len > cap) ? cap : max_seq_len;
+  DecodeWorkspace w{};
+  w.max_items = (int64_t)num_seqs * ((s + kChunkTokens - 1) / kChunkTokens);
+  size_t at = 0;
+  w.chunk_start_off = at;
+  at = align_up(at + sizeof(int32_t) * ((size_t)num_seqs + 1), 256);
+  w.items_off = at;
+  at = align_up(at + sizeof(int32_t) * 2 * (size_t)w.max_items, 256);
+  w.ml_off = at;
+  at = align_up(at + sizeof(float) * 2 * (size_t)w.max_items * p.num_q_heads, 256);
+  w.acc_off = at;
+  at = align_up(at + sizeof(float) * kPartialFloats * (size_t)w.max_items * p.num_q_heads, 256);
+  w.total_bytes = at;
+  return w;
+}
+
+// Host-side validation of the parameter struct; no HIP calls.
+inline int check_params(const vtc_attn_params* p) {
+  if (p == nullptr) return VTC_ERR_INVALID_ARG;
+  if (p->num_q_heads <= 0 || p->num_kv_heads <= 0 || p->max_blocks_per_seq <= 0) return VTC_ERR_INVALID_ARG;
+  if (!(p->scale == p->scale)) return VTC_ERR_INVALID_ARG;
+  if (p->num_q_heads % p->num_kv_heads != 0) return VTC_ERR_UNSUPPORTED;
+  const int g = p->num_q_heads / p->num_kv_heads;
+  if (g != 1 && g != 2 && g != 4 && g != 8) return VTC_ERR_UNSUPPORTED;
+  if (p->head_dim != kHeadDim || p->block_size != kBlockSize) return VTC_ERR_UNSUPPORTED;
+  if (p->dtype != VTC_F16 && p->dtype != VTC_BF16) return VTC_ERR_UNSUPPORTED;
+  return VTC_OK;
+}
+
+int device_cu_count();   // compute units of the current device (cached per device)
+
+// Kernel launchers (one translation unit each).
+int launch_decode(const vtc_attn_params& p, int32_t num_seqs, const void* q, const void* k_cache,
+                  const void* v_cache, const int32_t* block_table, const int32_t* seq_lens, void* out,
+                  void* workspace, hipStream_t stream, hipEvent_t ev_begin, hipEvent_t ev_end);
+int launch_prefill(const vtc_attn_params& p, int32_t num_seqs, const void* q, const int32_t* cu_q_lens,
+                   int32_t max_q_len, const void* k_cache, const void* v_cache, const int32_t* block_table,
+                   const int32_t* seq_lens, void* out, hipStream_t stream);
+int launch_counter_update(int64_t* counters, int32_t num_clients, const int32_t* client_ids,
+                          const int32_t* n_in, const int32_t* n_out, int32_t n, int64_t w_p, int64_t w_q,
+                          hipStream_t stream);
+int launch_gather_slots(const vtc_attn_params& p, int32_t num_seqs, const int32_t* block_table,
+                        const int32_t* seq_lens, const int32_t* cu_out, int32_t max_seq_len,
+                        int32_t* slots_out, hipStream_t stream);
+
+}  // namespace vtc

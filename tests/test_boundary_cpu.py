@@ -1,0 +1,131 @@
+"""The C ABI without a GPU: the library loads, exports what include/vtc.h declares,
+and rejects bad host-visible arguments before touching the device."""
+import ctypes
+import os
+import re
+
+import pytest
+
+import paper_2401_00588_amd as vtc
+from paper_2401_00588_amd.binding import AttnParams
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+@pytest.fixture(scope="module")
+def lib():
+    if not os.path.exists(vtc.library_path()):
+        from paper_2401_00588_amd import build
+        build.build()
+    return vtc.load_library()
+
+
+def _declared_symbols():
+    text = open(os.path.join(ROOT, "include", "vtc.h"), encoding="utf-8").read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(vtc_[a-z_0-9]+)\s*\(", text)))
+
+
+def test_every_declared_symbol_is_exported(lib):
+    names = _declared_symbols()
+    assert {"vtc_attn_decode", "vtc_attn_prefill_chunk", "vtc_counter_update", "vtc_attn_workspace_bytes",
+            "vtc_debug_gather_slots", "vtc_strerror", "vtc_version"} <= set(names)
+    for name in names:
+        assert getattr(lib, name) is not None
+
+
+def test_version_and_strerror(lib):
+    assert vtc.vtc_version() >= 100
+    for code in (0, -1, -2, -3, -4, -99):
+        assert isinstance(vtc.vtc_strerror(code), str) and vtc.vtc_strerror(code)
+    assert vtc.vtc_strerror(0) == "success"
+
+
+def good_params(**kw):
+    base = dict(num_q_heads=32, num_kv_heads=8, head_dim=128, block_size=16, max_blocks_per_seq=256,
+                dtype=vtc.VTC_BF16, scale=0.0883883461356163)
+    base.update(kw)
+    return AttnParams(**base)
+
+
+def test_workspace_bytes_is_host_arithmetic(lib):
+    p = good_params()
+    small = vtc.vtc_attn_workspace_bytes(p, 8, 256)
+    big = vtc.vtc_attn_workspace_bytes(p, 512, 4096)
+    full = vtc.vtc_attn_workspace_bytes(p, 512, 0)
+    assert 0 < small < big == full
+    assert vtc.vtc_attn_workspace_bytes(p, 512, 10 ** 9) == full        # clamped to the table capacity
+    assert big % 256 == 0
+    # at least one fp32 partial (128 floats + m, l) per (chunk of <= 256 tokens, q head)
+    assert big >= 512 * (4096 // 256) * 32 * (128 + 2) * 4
+    assert vtc.vtc_attn_workspace_bytes(good_params(head_dim=64), 8, 256) == 0
+    assert lib.vtc_attn_workspace_bytes(None, 8, 256) == 0
+
+
+@pytest.mark.parametrize("kw,code", [
+    (dict(head_dim=64), -2), (dict(block_size=32), -2), (dict(dtype=7), -2),
+    (dict(num_q_heads=32, num_kv_heads=5), -2), (dict(num_q_heads=48, num_kv_heads=16), -2),
+    (dict(num_q_heads=0), -1), (dict(num_kv_heads=-1), -1), (dict(max_blocks_per_seq=0), -1),
+    (dict(scale=float("nan")), -1),
+])
+def test_bad_params_are_rejected_by_every_attention_entry_point(lib, kw, code):
+    p = good_params(**kw)
+    one = ctypes.c_void_p(256)   # never dereferenced: validation fails first
+    assert lib.vtc_attn_decode(ctypes.byref(p), 1, one, one, one, one, one, one, one, 1 << 30, None) == code
+    assert lib.vtc_attn_prefill_chunk(ctypes.byref(p), 1, one, one, 1, one, one, one, one, one, None, 0, None) == code
+    assert lib.vtc_debug_gather_slots(ctypes.byref(p), 1, one, one, one, 1, one, None) == code
+
+
+def test_null_pointers_sizes_alignment_and_workspace(lib):
+    p = good_params()
+    a = ctypes.c_void_p(4096)
+    need = vtc.vtc_attn_workspace_bytes(p, 4, 0)
+    assert lib.vtc_attn_decode(None, 4, a, a, a, a, a, a, a, need, None) == -1
+    assert lib.vtc_attn_decode(ctypes.byref(p), -1, a, a, a, a, a, a, a, need, None) == -1
+    assert lib.vtc_attn_decode(ctypes.byref(p), 0, None, None, None, None, None, None, None, 0, None) == 0
+    for hole in range(7):
+        args = [a] * 7
+        args[hole] = None
+        assert lib.vtc_attn_decode(ctypes.byref(p), 4, *args, need, None) == -1
+    assert lib.vtc_attn_decode(ctypes.byref(p), 4, a, a, a, a, a, a, a, need - 1, None) == -3
+    assert lib.vtc_attn_decode(ctypes.byref(p), 4, a, a, a, a, a, a, ctypes.c_void_p(4096 + 64), need, None) == -1
+    assert lib.vtc_attn_decode(ctypes.byref(p), 4, ctypes.c_void_p(4098), a, a, a, a, a, a, need, None) == -1
+
+    assert lib.vtc_attn_prefill_chunk(ctypes.byref(p), 0, None, None, 0, None, None, None, None, None, None, 0, None) == 0
+    assert lib.vtc_attn_prefill_chunk(ctypes.byref(p), 2, a, a, 0, a, a, a, a, a, None, 0, None) == 0
+    assert lib.vtc_attn_prefill_chunk(ctypes.byref(p), 2, a, a, -1, a, a, a, a, a, None, 0, None) == -1
+    for hole in (0, 1, 3, 4, 5, 6, 7):
+        args = [a, a, 16, a, a, a, a, a]
+        args[hole] = None
+        assert lib.vtc_attn_prefill_chunk(ctypes.byref(p), 2, *args, None, 0, None) == -1
+
+    assert lib.vtc_counter_update(None, 4, a, a, a, 8, 1, 2, None) == -1
+    assert lib.vtc_counter_update(a, 4, None, a, a, 8, 1, 2, None) == -1
+    assert lib.vtc_counter_update(a, -1, a, a, a, 8, 1, 2, None) == -1
+    assert lib.vtc_counter_update(a, 4, a, a, a, -8, 1, 2, None) == -1
+    assert lib.vtc_counter_update(None, 4, None, None, None, 0, 1, 2, None) == 0
+
+    assert lib.vtc_debug_gather_slots(ctypes.byref(p), 2, a, a, a, -1, a, None) == -1
+    assert lib.vtc_debug_gather_slots(ctypes.byref(p), 2, None, a, a, 5, a, None) == -1
+    assert lib.vtc_debug_gather_slots(ctypes.byref(p), 0, None, None, None, 0, None, None) == 0
+
+
+def test_wrappers_refuse_cpu_tensors(lib):
+    import torch
+
+    p = good_params()
+    q = torch.zeros(1, 32, 128, dtype=torch.bfloat16)
+    kc = torch.zeros(2, 8, 16, 128, dtype=torch.bfloat16)
+    with pytest.raises(ValueError):
+        vtc.vtc_attn_decode(p, q, kc, kc, torch.zeros(1, 256, dtype=torch.int32), torch.ones(1, dtype=torch.int32))
+    with pytest.raises(ValueError):
+        vtc.vtc_counter_update(torch.zeros(2, dtype=torch.int64), torch.zeros(3, dtype=torch.int32), None, None, 1, 2)
+
+
+def test_missing_library_is_a_loud_error(monkeypatch):
+    from paper_2401_00588_amd import binding
+
+    monkeypatch.setattr(binding, "_lib", None)
+    monkeypatch.setattr(binding, "_LIB_NAME", "libvtc_not_built.so")
+    with pytest.raises(RuntimeError, match="no CPU fallback"):
+        binding.load_library()

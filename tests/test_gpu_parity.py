@@ -1,0 +1,310 @@
+"""Parity of the HIP path with the CPU oracle, through the C ABI (needs an MI355X).
+
+Tolerances (max-abs against the *unrounded* fp64 oracle): 2e-3 for fp16, 1e-2 for
+bf16.  Counters and slot indices are compared bit for bit.
+"""
+import math
+import sys
+
+import numpy as np
+import pytest
+
+import paper_2401_00588_amd as vtc
+from oracle import attention as OA
+from oracle.counters import counter_update as oracle_counter_update
+from oracle.counters import gather_slots as oracle_gather_slots
+from workloads import (NAN_BITS, bits_to_tensor, make_block_table, make_device_step, make_qkv_numpy,
+                       make_step_batch, poison_unused_rows, sequence_rows_to_host, tensor_to_bits)
+
+pytestmark = pytest.mark.gpu
+
+TOL = {"f16": 2e-3, "bf16": 1e-2}
+SCALE = 1.0 / math.sqrt(128.0)
+
+
+def say(msg):
+    print(msg, flush=True)
+    sys.stdout.flush()
+
+
+@pytest.fixture(scope="module")
+def torch():
+    import torch as t
+
+    assert t.cuda.is_available(), "these tests need a GPU"
+    vtc.load_library()
+    return t
+
+
+def _i32(torch, a):
+    return torch.from_numpy(np.ascontiguousarray(a, dtype=np.int32)).cuda()
+
+
+# ------------------------------------------------------------------ counters
+@pytest.mark.parametrize("n,clients,seed", [(8, 2, 0), (64, 2, 1), (256, 4, 2), (512, 27, 3), (272, 8, 4),
+                                            (1, 1, 5), (5000, 27, 6), (20000, 5000, 7), (4097, 4096, 8)])
+def test_counter_update_is_bit_exact(torch, n, clients, seed):
+    say(f"counter_update n={n} clients={clients} seed={seed}")
+    rng = np.random.default_rng(seed)
+    ids = rng.integers(-2, clients + 2, size=n).astype(np.int32)       # some ids out of range on both sides
+    n_in = rng.integers(0, 4097, size=n).astype(np.int32)
+    n_out = rng.integers(0, 2, size=n).astype(np.int32)
+    base = rng.integers(0, 1 << 40, size=clients).astype(np.int64)
+    for w_p, w_q, use_in, use_out in ((1, 2, True, True), (1, 2, False, True), (3, 5, True, False), (7, 11, False, False)):
+        c = torch.from_numpy(base.copy()).cuda()
+        vtc.vtc_counter_update(c, _i32(torch, ids), _i32(torch, n_in) if use_in else None,
+                               _i32(torch, n_out) if use_out else None, w_p, w_q)
+        want = oracle_counter_update(base, ids, n_in if use_in else None, n_out if use_out else None, w_p, w_q)
+        assert c.cpu().tolist() == want
+
+
+def test_counter_update_negative_tokens_and_repeated_steps(torch):
+    say("counter_update refunds / repeated steps")
+    rng = np.random.default_rng(11)
+    ids = rng.integers(0, 3, size=40).astype(np.int32)
+    n_out = rng.integers(-50, 50, size=40).astype(np.int32)
+    c = torch.zeros(3, dtype=torch.int64).cuda()
+    want = [0, 0, 0]
+    for _ in range(5):
+        vtc.vtc_counter_update(c, _i32(torch, ids), None, _i32(torch, n_out), 1, 2)
+        want = oracle_counter_update(want, ids, None, n_out, 1, 2)
+    assert c.cpu().tolist() == want
+
+
+@pytest.mark.parametrize("cfg", [1, 2, 3, 4, 5])
+def test_counter_update_on_the_config_batches(torch, cfg):
+    say(f"counter_update config {cfg}")
+    b = make_step_batch(cfg)
+    ids, n_in, n_out = b.counter_update_args()
+    c = torch.from_numpy(b.counters_before.copy()).cuda()
+    vtc.vtc_counter_update(c, _i32(torch, ids), _i32(torch, n_in), _i32(torch, n_out), b.w_p, b.w_q)
+    want = oracle_counter_update(b.counters_before, ids, n_in, n_out, b.w_p, b.w_q)
+    assert c.cpu().tolist() == want
+    if b.counters_after is not None and b.num_prefill == 0:
+        assert want == b.counters_after.tolist()        # what the CPU scheduler recorded for this step
+
+
+# --------------------------------------------------------------------- slots
+def test_gathered_slots_are_bit_exact(torch):
+    say("gather_slots")
+    rng = np.random.default_rng(21)
+    seq = np.array([0, 1, 15, 16, 17, 255, 256, 257, 1000, 4096], dtype=np.int32)
+    table, nb = make_block_table(rng, seq, 16)
+    p = vtc.make_params(32, 8, 128, 16, table.shape[1], "bf16", SCALE)
+    cu = np.concatenate([[0], np.cumsum(seq)]).astype(np.int32)
+    out = torch.full((int(cu[-1]),), -1, dtype=torch.int32).cuda()
+    vtc.vtc_debug_gather_slots(p, _i32(torch, table), _i32(torch, seq), _i32(torch, cu), int(seq.max()), out)
+    assert out.cpu().tolist() == oracle_gather_slots(table, seq, 16)
+
+
+# -------------------------------------------------------------------- decode
+def _decode_case(torch, seq_lens, hq, hkv, dtype, seed, poison=False, min_row_len=0):
+    rng = np.random.default_rng(seed)
+    table, nb = make_block_table(rng, seq_lens, 16, min_row_len=min_row_len)
+    q, k, v = make_qkv_numpy(rng, len(seq_lens), hq, hkv, 128, nb, 16, dtype)
+    if poison:
+        poison_unused_rows(k, table, seq_lens, NAN_BITS[dtype])
+        poison_unused_rows(v, table, seq_lens, NAN_BITS[dtype])
+    p = vtc.make_params(hq, hkv, 128, 16, table.shape[1], dtype, SCALE)
+    out = vtc.vtc_attn_decode(p, bits_to_tensor(q, dtype), bits_to_tensor(k, dtype), bits_to_tensor(v, dtype),
+                              _i32(torch, table), _i32(torch, seq_lens))
+    torch.cuda.synchronize()
+    got = OA.widen(tensor_to_bits(out), dtype)
+    want = OA.paged_decode(q, k, v, table, seq_lens, SCALE, dtype)
+    return got, want
+
+
+RAGGED = [1, 2, 3, 4, 5, 15, 16, 17, 31, 32, 33, 100, 255, 256, 257, 300, 511, 512, 513, 700, 1023, 1025]
+
+
+@pytest.mark.parametrize("dtype,hq,hkv", [("f16", 32, 32), ("bf16", 32, 8), ("f16", 8, 4), ("bf16", 16, 2),
+                                          ("bf16", 4, 4), ("f16", 32, 8)])
+def test_decode_ragged_lengths_match_the_oracle(torch, dtype, hq, hkv):
+    say(f"decode ragged dtype={dtype} Hq={hq} Hkv={hkv}")
+    got, want = _decode_case(torch, RAGGED, hq, hkv, dtype, seed=31)
+    err = np.abs(got - want).max()
+    say(f"  max abs err {err:.3e}  max |o| {np.abs(want).max():.3f}")
+    assert np.isfinite(got).all() and err <= TOL[dtype]
+
+
+@pytest.mark.parametrize("dtype,hq,hkv", [("f16", 32, 32), ("bf16", 32, 8)])
+def test_decode_ignores_rows_past_seq_len_and_handles_empty_sequences(torch, dtype, hq, hkv):
+    say(f"decode poisoned tails dtype={dtype}")
+    seq = [0, 1, 7, 16, 0, 250, 257, 17]
+    got, want = _decode_case(torch, seq, hq, hkv, dtype, seed=32, poison=True, min_row_len=40)
+    assert np.isfinite(got).all()
+    assert np.abs(got - want).max() <= TOL[dtype]
+    assert (got[0] == 0).all() and (got[4] == 0).all()
+
+
+def test_decode_single_key_and_identical_keys(torch):
+    say("decode closed forms on the GPU")
+    rng = np.random.default_rng(33)
+    seq = [1, 200]
+    table, nb = make_block_table(rng, seq, 16)
+    q, k, v = make_qkv_numpy(rng, 2, 32, 32, 128, nb, 16, "f16")
+    for b in range(13):                         # sequence 1: every key identical -> mean of V
+        k[table[1, b]] = k[table[1, 0], :, :1, :]
+    p = vtc.make_params(32, 32, 128, 16, table.shape[1], "f16", SCALE)
+    out = vtc.vtc_attn_decode(p, bits_to_tensor(q, "f16"), bits_to_tensor(k, "f16"), bits_to_tensor(v, "f16"),
+                              _i32(torch, table), _i32(torch, seq))
+    got = OA.widen(tensor_to_bits(out), "f16")
+    v0 = OA.widen(v[table[0, 0], :, 0, :], "f16")
+    assert np.array_equal(got[0], v0)           # one key: the value itself, exactly
+    vals = np.stack([OA.gather_sequence(v, table[1], 200, h, "f16") for h in range(32)])  # [H, S, D]
+    assert np.abs(got[1] - vals.mean(axis=1)).max() <= 1e-3
+
+
+@pytest.mark.parametrize("cfg", [1, 2])
+def test_decode_small_configs_elementwise(torch, cfg):
+    say(f"decode config {cfg} (every output element)")
+    b = make_step_batch(cfg)
+    st = make_device_step(b, host_random=True)
+    sh = b.shape
+    p = vtc.make_params(sh.num_q_heads, sh.num_kv_heads, 128, 16, st.max_blocks_per_seq, sh.dtype, SCALE)
+    out = vtc.vtc_attn_decode(p, st.q, st.k_cache, st.v_cache, st.block_table, st.seq_lens)
+    torch.cuda.synchronize()
+    got = OA.widen(tensor_to_bits(out), sh.dtype)
+    want = OA.paged_decode(tensor_to_bits(st.q), tensor_to_bits(st.k_cache), tensor_to_bits(st.v_cache),
+                           st.block_table.cpu().numpy(), b.seq_lens, SCALE, sh.dtype)
+    err = np.abs(got - want).max()
+    say(f"  max abs err {err:.3e}")
+    assert err <= TOL[sh.dtype]
+
+
+def _sampled_decode_check(torch, st, out, n_samples, seed):
+    b = st.batch
+    sh = b.shape
+    rng = np.random.default_rng(seed)
+    order = np.argsort(b.seq_lens)
+    picks = list(order[:2]) + list(order[-2:]) + list(rng.choice(b.num_decode, size=n_samples, replace=False))
+    q_bits = tensor_to_bits(st.q)
+    got = OA.widen(tensor_to_bits(out), sh.dtype)
+    group = sh.num_q_heads // sh.num_kv_heads
+    worst = 0.0
+    for r in picks:
+        r = int(r)
+        h = int(rng.integers(0, sh.num_q_heads))
+        g = h // group
+        s = int(b.seq_lens[r])
+        keys = OA.widen(sequence_rows_to_host(st.k_cache, st.block_table[r], s, g), sh.dtype)
+        vals = OA.widen(sequence_rows_to_host(st.v_cache, st.block_table[r], s, g), sh.dtype)
+        want = OA.attend_one(OA.widen(q_bits[r, h], sh.dtype), keys, vals, SCALE)
+        worst = max(worst, float(np.abs(got[r, h] - want).max()))
+    return worst, got
+
+
+@pytest.mark.parametrize("cfg", [3, 4, 5])
+def test_decode_full_size_configs_on_sampled_rows(torch, cfg):
+    say(f"decode config {cfg} at full size (sampled rows, bench launch configuration)")
+    b = make_step_batch(cfg)
+    st = make_device_step(b)
+    sh = b.shape
+    p = vtc.make_params(sh.num_q_heads, sh.num_kv_heads, 128, 16, st.max_blocks_per_seq, sh.dtype, SCALE)
+    ws = torch.empty(vtc.vtc_attn_workspace_bytes(p, b.num_decode, 0), dtype=torch.uint8, device="cuda")
+    out = torch.full_like(st.q, float("nan"))
+    vtc.vtc_attn_decode(p, st.q, st.k_cache, st.v_cache, st.block_table, st.seq_lens, out=out, workspace=ws)
+    torch.cuda.synchronize()
+    worst, got = _sampled_decode_check(torch, st, out, n_samples=20, seed=cfg)
+    say(f"  worst sampled max abs err {worst:.3e}")
+    assert np.isfinite(got).all()               # every row was written
+    assert worst <= TOL[sh.dtype]
+    # a second call into the same workspace gives the same bits (no stale state, deterministic order)
+    out2 = torch.empty_like(st.q)
+    vtc.vtc_attn_decode(p, st.q, st.k_cache, st.v_cache, st.block_table, st.seq_lens, out=out2, workspace=ws)
+    torch.cuda.synchronize()
+    assert torch.equal(out.view(torch.int16), out2.view(torch.int16))
+
+
+# ------------------------------------------------------------------- prefill
+def _prefill_case(torch, q_lens, seq_lens, hq, hkv, dtype, seed, poison=False):
+    rng = np.random.default_rng(seed)
+    table, nb = make_block_table(rng, seq_lens, 16)
+    cu = np.concatenate([[0], np.cumsum(q_lens)]).astype(np.int32)
+    q, k, v = make_qkv_numpy(rng, int(cu[-1]), hq, hkv, 128, nb, 16, dtype)
+    if poison:
+        poison_unused_rows(k, table, seq_lens, NAN_BITS[dtype])
+        poison_unused_rows(v, table, seq_lens, NAN_BITS[dtype])
+    p = vtc.make_params(hq, hkv, 128, 16, table.shape[1], dtype, SCALE)
+    out = vtc.vtc_attn_prefill_chunk(p, bits_to_tensor(q, dtype), _i32(torch, cu), int(max(q_lens)),
+                                     bits_to_tensor(k, dtype), bits_to_tensor(v, dtype), _i32(torch, table),
+                                     _i32(torch, seq_lens))
+    torch.cuda.synchronize()
+    got = OA.widen(tensor_to_bits(out), dtype)
+    want = OA.paged_prefill_chunk(q, cu, k, v, table, seq_lens, SCALE, dtype)
+    return got, want
+
+
+PF_Q = [1, 5, 16, 17, 63, 64, 65, 100, 130, 256]
+PF_S = [1, 5, 16, 40, 63, 200, 65, 100, 400, 512]
+
+
+@pytest.mark.parametrize("dtype,hq,hkv", [("bf16", 8, 2), ("f16", 4, 4), ("bf16", 32, 8), ("f16", 8, 1)])
+def test_prefill_chunk_ragged_matches_the_oracle(torch, dtype, hq, hkv):
+    say(f"prefill ragged dtype={dtype} Hq={hq} Hkv={hkv}")
+    got, want = _prefill_case(torch, PF_Q, PF_S, hq, hkv, dtype, seed=41, poison=True)
+    err = np.abs(got - want)
+    say(f"  max abs err {err.max():.3e}  max |o| {np.abs(want).max():.3f}")
+    assert np.isfinite(got).all() and err.max() <= TOL[dtype]
+
+
+@pytest.mark.parametrize("chunk", [0, 1])
+def test_prefill_config5_chunks_on_sampled_rows_and_decode_consistency(torch, chunk):
+    say(f"prefill config 5 chunk {chunk} at full size")
+    b = make_step_batch(5, prefill_chunk=chunk)
+    st = make_device_step(b)
+    sh = b.shape
+    p = vtc.make_params(sh.num_q_heads, sh.num_kv_heads, 128, 16, st.max_blocks_per_seq, sh.dtype, SCALE)
+    out = torch.full_like(st.pf_q, float("nan"))
+    vtc.vtc_attn_prefill_chunk(p, st.pf_q, st.pf_cu_q_lens, st.pf_max_q_len, st.k_cache, st.v_cache,
+                               st.pf_block_table, st.pf_seq_lens, out=out)
+    torch.cuda.synchronize()
+    got = OA.widen(tensor_to_bits(out), sh.dtype)
+    assert np.isfinite(got).all()
+    rng = np.random.default_rng(50 + chunk)
+    q_bits = tensor_to_bits(st.pf_q)
+    cu = st.pf_cu_q_lens.cpu().numpy()
+    worst = 0.0
+    for _ in range(24):
+        r = int(rng.integers(0, b.num_prefill))
+        i = int(rng.choice([0, 1, 255, int(rng.integers(0, 256))]))
+        h = int(rng.integers(0, sh.num_q_heads))
+        g = h // (sh.num_q_heads // sh.num_kv_heads)
+        s = int(b.pf_seq_lens[r])
+        pos = s - int(b.pf_q_lens[r]) + i
+        keys = OA.widen(sequence_rows_to_host(st.k_cache, st.pf_block_table[r], pos + 1, g), sh.dtype)
+        vals = OA.widen(sequence_rows_to_host(st.v_cache, st.pf_block_table[r], pos + 1, g), sh.dtype)
+        want = OA.attend_one(OA.widen(q_bits[cu[r] + i, h], sh.dtype), keys, vals, SCALE)
+        worst = max(worst, float(np.abs(got[cu[r] + i, h] - want).max()))
+    say(f"  worst sampled max abs err {worst:.3e}")
+    assert worst <= TOL[sh.dtype]
+    # the last chunk token attends to the whole context: same answer as a decode call at that length
+    last_rows = (st.pf_cu_q_lens[1:] - 1).long()
+    q_last = st.pf_q[last_rows].contiguous()
+    dec = vtc.vtc_attn_decode(p, q_last, st.k_cache, st.v_cache, st.pf_block_table, st.pf_seq_lens)
+    torch.cuda.synchronize()
+    diff = (dec.double() - out[last_rows].double()).abs().max().item()
+    say(f"  prefill last row vs decode: {diff:.3e}")
+    assert diff <= 2 * TOL[sh.dtype]
+
+
+# ---------------------------------------------------------------- whole step
+def test_mixed_step_config5_on_one_stream(torch):
+    say("mixed step: prefill chunk + decode + one counter update")
+    b = make_step_batch(5)
+    st = make_device_step(b)
+    sh = b.shape
+    p = vtc.make_params(sh.num_q_heads, sh.num_kv_heads, 128, 16, st.max_blocks_per_seq, sh.dtype, SCALE)
+    stream = torch.cuda.Stream()
+    torch.cuda.synchronize()
+    with torch.cuda.stream(stream):
+        pf = vtc.vtc_attn_prefill_chunk(p, st.pf_q, st.pf_cu_q_lens, st.pf_max_q_len, st.k_cache, st.v_cache,
+                                        st.pf_block_table, st.pf_seq_lens)
+        dec = vtc.vtc_attn_decode(p, st.q, st.k_cache, st.v_cache, st.block_table, st.seq_lens)
+        vtc.vtc_counter_update(st.counters, st.cu_client_ids, st.cu_n_in, st.cu_n_out, b.w_p, b.w_q)
+    stream.synchronize()
+    ids, n_in, n_out = b.counter_update_args()
+    assert st.counters.cpu().tolist() == oracle_counter_update(b.counters_before, ids, n_in, n_out, b.w_p, b.w_q)
+    assert sum(st.counters.cpu().tolist()) == 1 * 16 * 512 + 2 * 256
+    worst, got = _sampled_decode_check(torch, st, dec, n_samples=8, seed=5)
+    assert worst <= TOL[sh.dtype] and torch.isfinite(pf.float()).all()

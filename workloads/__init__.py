@@ -15,3 +15,11 @@ from .tensors import (  # noqa: F401
     poison_unused_rows,
     NAN_BITS,
 )
+from .device import (  # noqa: F401,E402
+    DeviceStep,
+    bits_to_tensor,
+    make_device_step,
+    sequence_rows_to_host,
+    tensor_to_bits,
+    torch_dtype,
+)
