@@ -37,7 +37,11 @@ def parse_args():
     ap.add_argument("--workload", default="cfg3", choices=["cfg2", "cfg3", "cfg4", "cfg5"])
     ap.add_argument("--prefill-chunk", type=int, default=1, choices=[0, 1], help="cfg5: which 256-token chunk")
     ap.add_argument("--no-cpu-baseline", action="store_true")
-    ap.add_argument("--cpu-sample-requests", type=int, default=12)
+    ap.add_argument("--cpu-sample-requests", type=int, default=256,
+                    help="decode requests handed to the CPU oracle (default: the whole cfg3 batch, ~20 core-seconds)")
+    ap.add_argument("--calibrate-copy", action="store_true",
+                    help="instead of the benchmark, run a plain 1 GiB device copy a few times "
+                         "(reference dispatch of known size for scaling rocprofv3 byte counters)")
     return ap.parse_args()
 
 
@@ -121,6 +125,15 @@ def main() -> int:
         print("bench.py: no GPU visible", file=sys.stderr)
         return 2
     torch.cuda.set_device(0)
+    if args.calibrate_copy:
+        n = 1 << 30
+        src = torch.empty(n, dtype=torch.uint8, device="cuda").random_(0, 256)
+        dst = torch.empty_like(src)
+        for _ in range(4):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+        print(json.dumps({"calibration": "device copy", "bytes_read": n, "bytes_written": n, "dispatches": 4}))
+        return 0
     cfg = int(args.workload[3:])
     batch = make_step_batch(cfg, prefill_chunk=args.prefill_chunk) if cfg == 5 else make_step_batch(cfg)
     st = make_device_step(batch)

@@ -33,16 +33,17 @@ def _hipcc() -> str:
     raise RuntimeError("hipcc not found")
 
 
-def build(verbose: bool = False) -> str:
-    os.makedirs(BUILD_DIR, exist_ok=True)
+def build(verbose: bool = False, extra_flags=(), output: str = LIB, build_dir: str = BUILD_DIR) -> str:
+    """Compile every csrc/*.hip and link ``output``.  ``extra_flags`` (e.g. -D tunables) are for experiments."""
+    os.makedirs(build_dir, exist_ok=True)
     sources = sorted(glob.glob(os.path.join(CSRC, "*.hip")))
     if not sources:
         raise RuntimeError(f"no .hip sources under {CSRC}")
     hipcc = _hipcc()
 
     def compile_one(src: str) -> str:
-        obj = os.path.join(BUILD_DIR, os.path.basename(src).replace(".hip", ".o"))
-        cmd = [hipcc, *FLAGS, "-c", src, "-o", obj]
+        obj = os.path.join(build_dir, os.path.basename(src).replace(".hip", ".o"))
+        cmd = [hipcc, *FLAGS, *extra_flags, "-c", src, "-o", obj]
         res = subprocess.run(cmd, capture_output=True, text=True)
         noise = "is not a recognized feature for this target"
         err = "\n".join(ln for ln in res.stderr.splitlines() if noise not in ln)
@@ -54,11 +55,11 @@ def build(verbose: bool = False) -> str:
 
     with ThreadPoolExecutor(max_workers=min(8, len(sources))) as pool:
         objects = list(pool.map(compile_one, sources))
-    cmd = [hipcc, "--offload-arch=gfx950", "-shared", "-fPIC", "-fno-gpu-rdc", *objects, "-o", LIB]
+    cmd = [hipcc, "--offload-arch=gfx950", "-shared", "-fPIC", "-fno-gpu-rdc", *objects, "-o", output]
     res = subprocess.run(cmd, capture_output=True, text=True)
     if res.returncode != 0:
         raise RuntimeError(f"link failed:\n{res.stderr}")
-    return LIB
+    return output
 
 
 if __name__ == "__main__":

@@ -3,35 +3,52 @@
 // request against all of its cached tokens).  HBM-bound: every cached K and V
 // element of every running request is read exactly once per step.
 //
-// Decomposition
-//   plan    one workgroup: chunks per sequence -> exclusive prefix -> a flat list
-//           of work items (sequence, chunk).  A chunk is kChunkTokens tokens.
-//   attend  one 64-lane wavefront per (work item, kv head), in a grid-stride loop.
-//           The wave streams the chunk's K and V tiles (4 KiB each per block) with
-//           16-byte loads that are contiguous across the wave, keeps an online
-//           softmax per 16-lane row, and either writes the final output (sequence
-//           has a single chunk) or an fp32 partial (m, l, acc[128]).
-//   merge   one workgroup per (sequence, q head) with more than one chunk: combines
-//           the partials exactly (rescale by exp2(m_c - m)) and writes the output;
-//           writes zeros for empty sequences.
+// Decomposition.  Order all (sequence r, kv head h, KV block b) triples of the batch
+// as r-major, then h, then b, and call that sequence of gtot blocks the *stream*.
+// The stream is cut into W equal ranges, one per resident wavefront, regardless of
+// where sequences begin and end, so every wave moves the same number of bytes:
+//   plan    one workgroup: blocks per sequence -> exclusive prefix; then for each
+//           wave the (r, h, b) at which its range starts and the range length.
+//   attend  one 64-lane wave per range.  The wave walks its range block by block,
+//           always one block of loads ahead of the arithmetic, across sequence and
+//           head boundaries without draining.  Each maximal run of blocks of one
+//           (r, h) inside the range is a *piece*; when a piece ends the wave writes
+//           either the final output (the piece is the whole sequence) or an fp32
+//           partial (m, l, acc[128] per q head).  A wave owns at most two partial
+//           pieces: one cut at its range start and one cut at its range end.
+//   merge   one wave per (r, q head): finds the waves whose ranges overlap the
+//           sequence, combines their partials exactly (rescale by exp2(m_c - m))
+//           and writes the output; writes zeros for empty sequences.
 //
 // Lane mapping inside a wave: lane = 16 * row + sub.  A 16-byte load instruction
 // covers 4 tokens x 128 dims: row picks the token (4 * i + row for load i of a
 // block), sub picks dims 8*sub .. 8*sub+7.  A K.q dot product is 4 packed dot2
 // operations per lane plus a 4-step DPP all-reduce inside the 16-lane row; the V
 // update needs no cross-lane traffic.  The 4 rows keep separate softmax states
-// that are merged once per work item.
+// that are merged once per piece.
 #include "vtc_internal.h"
 
 namespace vtc {
 
 constexpr int kPlanThreads = 1024;
 
+// 64-bit helpers shared by plan and merge: start of wave w's range, and the wave that owns block g.
+__device__ __forceinline__ long long range_start(long long gtot, int waves, int w) {
+  return gtot * (long long)w / (long long)waves;
+}
+__device__ __forceinline__ int wave_of(long long gtot, int waves, long long g) {
+  int w = (int)(g * (long long)waves / gtot);
+  if (w + 1 < waves && range_start(gtot, waves, w + 1) <= g) ++w;
+  return w;
+}
+
 // ------------------------------------------------------------------ plan ----
 __global__ __launch_bounds__(kPlanThreads) void decode_plan_kernel(const int32_t* __restrict__ seq_lens,
-                                                                   int32_t num_seqs, int32_t max_tokens,
-                                                                   int32_t* __restrict__ chunk_start,
-                                                                   int2* __restrict__ items) {
+                                                                   int32_t num_seqs, int32_t num_kv_heads,
+                                                                   int32_t max_tokens, int32_t max_waves,
+                                                                   DecodeHeader* __restrict__ header,
+                                                                   int32_t* __restrict__ seg_prefix,
+                                                                   int4* __restrict__ wave_desc) {
   __shared__ int32_t scan[kPlanThreads];
   __shared__ int32_t carry;
   if (threadIdx.x == 0) carry = 0;
@@ -39,10 +56,7 @@ __global__ __launch_bounds__(kPlanThreads) void decode_plan_kernel(const int32_t
   for (int base = 0; base < num_seqs; base += kPlanThreads) {
     const int r = base + (int)threadIdx.x;
     int32_t n = 0;
-    if (r < num_seqs) {
-      const int32_t s = min(max(seq_lens[r], 0), max_tokens);
-      n = (s + kChunkTokens - 1) / kChunkTokens;
-    }
+    if (r < num_seqs) n = (min(max(seq_lens[r], 0), max_tokens) + kBlockSize - 1) / kBlockSize;
     scan[threadIdx.x] = n;
     __syncthreads();
     for (int off = 1; off < kPlanThreads; off <<= 1) {     // inclusive Hillis-Steele scan
@@ -51,30 +65,63 @@ __global__ __launch_bounds__(kPlanThreads) void decode_plan_kernel(const int32_t
       scan[threadIdx.x] += v;
       __syncthreads();
     }
-    const int32_t start = carry + scan[threadIdx.x] - n;
-    if (r < num_seqs) {
-      chunk_start[r] = start;
-      for (int c = 0; c < n; ++c) items[start + c] = make_int2(r, c);
-    }
+    if (r < num_seqs) seg_prefix[r] = carry + scan[threadIdx.x] - n;
     __syncthreads();
     if (threadIdx.x == kPlanThreads - 1) carry += scan[threadIdx.x];
     __syncthreads();
   }
-  if (threadIdx.x == 0) chunk_start[num_seqs] = carry;
+  const int32_t total_blocks = carry;
+  if (threadIdx.x == 0) seg_prefix[num_seqs] = total_blocks;
+  const long long gtot = (long long)total_blocks * num_kv_heads;
+  // every active wave gets at least kMinBlocksPerWave blocks
+  const long long want = (gtot + kMinBlocksPerWave - 1) / kMinBlocksPerWave;
+  const int waves = (int)(want < (long long)max_waves ? want : (long long)max_waves);
+  if (threadIdx.x == 0) {
+    header->gtot = gtot;
+    header->waves = waves;
+  }
+  __threadfence();
+  __syncthreads();                                           // seg_prefix is complete and visible
+  for (int w = threadIdx.x; w < max_waves; w += kPlanThreads) {
+    int4 d = make_int4(0, 0, 0, 0);
+    if (w < waves) {
+      const long long g = range_start(gtot, waves, w);
+      const long long n = range_start(gtot, waves, w + 1) - g;
+      // the sequence r with seg_prefix[r] * Hkv <= g < seg_prefix[r+1] * Hkv
+      int lo = 0, hi = num_seqs - 1;
+      while (lo < hi) {
+        const int mid = (lo + hi) >> 1;
+        if ((long long)seg_prefix[mid + 1] * num_kv_heads > g) hi = mid; else lo = mid + 1;
+      }
+      const int nb = seg_prefix[lo + 1] - seg_prefix[lo];
+      const long long off = g - (long long)seg_prefix[lo] * num_kv_heads;
+      d = make_int4(lo, (int)(off / nb), (int)(off % nb), (int)n);
+    }
+    wave_desc[w] = d;
+  }
 }
 
 // ---------------------------------------------------------------- attend ----
-template <typename T, int G>
+template <int G>
 struct RowState {
   float m[G];        // running max of the scaled logits (log2 domain)
   float l[G];        // running sum of exp2(logit - m)
   float acc[G][8];   // running sum of exp2(logit - m) * v, dims 8*sub .. 8*sub+7
+  __device__ __forceinline__ void reset() {
+#pragma unroll
+    for (int g = 0; g < G; ++g) {
+      m[g] = -INFINITY;
+      l[g] = 0.f;
+#pragma unroll
+      for (int e = 0; e < 8; ++e) acc[g][e] = 0.f;
+    }
+  }
 };
 
 // Process one K/V block (16 tokens).  `nvalid` < 16 marks a ragged last block:
 // tokens >= nvalid are excluded and their (possibly garbage) V rows zeroed.
 template <typename T, int G, bool kTail>
-__device__ __forceinline__ void block_update(RowState<T, G>& st, const u32x4 (&q)[G], const u32x4 (&k)[4],
+__device__ __forceinline__ void block_update(RowState<G>& st, const u32x4 (&q)[G], const u32x4 (&k)[4],
                                              u32x4 (&v)[4], float scale2, int row, int nvalid) {
   float s[G][4];
 #pragma unroll
@@ -130,94 +177,98 @@ __device__ __forceinline__ void block_update(RowState<T, G>& st, const u32x4 (&q
 __device__ __forceinline__ void load_tile(u32x4 (&dst)[4], const uint16_t* __restrict__ tile, int lane) {
   const u32x4* src = reinterpret_cast<const u32x4*>(tile) + lane;
 #pragma unroll
-  for (int i = 0; i < 4; ++i) dst[i] = src[i * kWave];
+  for (int i = 0; i < 4; ++i) {
+#if VTC_DECODE_NT_LOADS
+    dst[i] = __builtin_nontemporal_load(src + i * kWave);     // streamed once: keep it out of the caches' way
+#else
+    dst[i] = src[i * kWave];
+#endif
+  }
 }
+
+// A position in the stream: which block, and where its K/V tile lives.
+struct StreamPos {
+  int r, h, b;       // sequence, kv head, block index inside the sequence
+  int nb;            // blocks of sequence r
+  int s_len;         // context length of sequence r (clamped)
+  size_t off;        // element offset of the (block, head) tile in k_cache / v_cache
+};
 
 template <typename T, int G>
 __global__ __launch_bounds__(kWave) void decode_attend_kernel(
     const uint16_t* __restrict__ q, const uint16_t* __restrict__ k_cache, const uint16_t* __restrict__ v_cache,
     const int32_t* __restrict__ block_table, const int32_t* __restrict__ seq_lens, uint16_t* __restrict__ out,
-    const int32_t* __restrict__ chunk_start, const int2* __restrict__ items, float2* __restrict__ part_ml,
-    float* __restrict__ part_acc, int32_t num_seqs, int32_t num_kv_heads, int32_t max_blocks_per_seq, float scale2) {
+    const int4* __restrict__ wave_desc, float2* __restrict__ part_ml, float* __restrict__ part_acc,
+    int32_t num_kv_heads, int32_t max_blocks_per_seq, float scale2) {
   const int lane = threadIdx.x;
   const int row = lane >> 4;
   const int sub = lane & 15;
   const int num_q_heads = num_kv_heads * G;
   const int max_tokens = max_blocks_per_seq * kBlockSize;
-  const uint32_t total = (uint32_t)chunk_start[num_seqs] * (uint32_t)num_kv_heads;
+  const int wave = blockIdx.x;
+  const int4 desc = wave_desc[wave];
+  const int n_blocks = desc.w;
+  if (n_blocks <= 0) return;
+  const size_t block_stride = (size_t)num_kv_heads * kTileElems;
 
-  for (uint32_t w = blockIdx.x; w < total; w += gridDim.x) {
-    const int slot = (int)(w / (uint32_t)num_kv_heads);  // index into items / partials
-    const int kvh = (int)(w - (uint32_t)slot * (uint32_t)num_kv_heads);
-    const int2 item = items[slot];
-    const int r = item.x;
-    const int c = item.y;
-    const int s_len = min(seq_lens[r], max_tokens);
-    const int n_chunks = (s_len + kChunkTokens - 1) / kChunkTokens;
-    const int t0 = c * kChunkTokens;
-    const int t1 = min(s_len, t0 + kChunkTokens);
-    const int n_full = (t1 - t0) / kBlockSize;          // complete blocks in this chunk
-    const int tail = (t1 - t0) % kBlockSize;            // valid tokens of the ragged last block
-    const int32_t* __restrict__ table = block_table + (size_t)r * max_blocks_per_seq + t0 / kBlockSize;
-
-    u32x4 qreg[G];
+  auto locate = [&](StreamPos& p) {        // fill in the tile offset of p
+    p.off = (size_t)block_table[(size_t)p.r * max_blocks_per_seq + p.b] * block_stride + (size_t)p.h * kTileElems;
+  };
+  auto step = [&](StreamPos& p) {          // move p to the next block of the stream (there is one)
+    if (++p.b == p.nb) {
+      p.b = 0;
+      if (++p.h == num_kv_heads) {
+        p.h = 0;
+        do {
+          ++p.r;
+          p.s_len = min(max(seq_lens[p.r], 0), max_tokens);
+          p.nb = (p.s_len + kBlockSize - 1) / kBlockSize;
+        } while (p.nb == 0);
+      }
+    }
+    locate(p);
+  };
+  auto load_q = [&](u32x4 (&dst)[G], const StreamPos& p) {
 #pragma unroll
     for (int g = 0; g < G; ++g)
-      qreg[g] = *reinterpret_cast<const u32x4*>(q + ((size_t)r * num_q_heads + kvh * G + g) * kHeadDim + sub * 8);
+      dst[g] = *reinterpret_cast<const u32x4*>(q + ((size_t)p.r * num_q_heads + p.h * G + g) * kHeadDim + sub * 8);
+  };
 
-    RowState<T, G> st;
-#pragma unroll
-    for (int g = 0; g < G; ++g) {
-      st.m[g] = -INFINITY;
-      st.l[g] = 0.f;
-#pragma unroll
-      for (int e = 0; e < 8; ++e) st.acc[g][e] = 0.f;
-    }
+  // cur: the block being consumed; nxt: the block whose loads are in flight; far: one further, so
+  // that its (scalar) block-table lookup is never waited for between a tile's loads and their use.
+  StreamPos cur;
+  cur.r = desc.x;
+  cur.h = desc.y;
+  cur.b = desc.z;
+  cur.s_len = min(max(seq_lens[cur.r], 0), max_tokens);
+  cur.nb = (cur.s_len + kBlockSize - 1) / kBlockSize;
+  locate(cur);
+  StreamPos nxt = cur, far = cur;
+  if (n_blocks > 1) {
+    step(nxt);
+    far = nxt;
+  }
+  if (n_blocks > 2) step(far);
 
-    const int n_blocks = n_full + (tail ? 1 : 0);
-    const int last = n_blocks - 1;
-    const size_t head_off = (size_t)kvh * kTileElems;
-    const size_t block_stride = (size_t)num_kv_heads * kTileElems;
-    // Two register buffers, used alternately; block ids are fetched two blocks ahead so
-    // that the (scalar) table lookup never sits between a tile's loads and their use.
-    u32x4 ka[4], va[4], kb[4], vb[4];
-    int32_t id_next = table[min(1, last)];
-    int32_t id_after = table[min(2, last)];
-    {
-      const size_t off = (size_t)table[0] * block_stride + head_off;
-      load_tile(ka, k_cache + off, lane);
-      load_tile(va, v_cache + off, lane);
-    }
-    int b = 0;
-    while (b < n_full) {
-      if (b + 1 < n_blocks) {                            // fetch block b+1 while block b is consumed
-        const size_t off = (size_t)id_next * block_stride + head_off;
-        load_tile(kb, k_cache + off, lane);
-        load_tile(vb, v_cache + off, lane);
-      }
-      id_next = id_after;
-      id_after = table[min(b + 3, last)];
-      block_update<T, G, false>(st, qreg, ka, va, scale2, row, kBlockSize);
-      ++b;
-      if (b >= n_full) {
-#pragma unroll
-        for (int i = 0; i < 4; ++i) {
-          ka[i] = kb[i];
-          va[i] = vb[i];
-        }
-        break;
-      }
-      if (b + 1 < n_blocks) {
-        const size_t off = (size_t)id_next * block_stride + head_off;
-        load_tile(ka, k_cache + off, lane);
-        load_tile(va, v_cache + off, lane);
-      }
-      id_next = id_after;
-      id_after = table[min(b + 3, last)];
-      block_update<T, G, false>(st, qreg, kb, vb, scale2, row, kBlockSize);
-      ++b;
-    }
-    if (tail) block_update<T, G, true>(st, qreg, ka, va, scale2, row, tail);
+  u32x4 qreg[G], qnext[G];
+  load_q(qreg, cur);
+  RowState<G> st;
+  st.reset();
+  int piece_lo = cur.b;                    // first block of the current piece
+
+  u32x4 ka[4], va[4], kb[4], vb[4];
+  load_tile(ka, k_cache + cur.off, lane);
+  load_tile(va, v_cache + cur.off, lane);
+
+  // Consume the block at `cur` from (kx, vx); close the piece if it ends here.
+  auto consume = [&](u32x4 (&kx)[4], u32x4 (&vx)[4], bool last_of_range) {
+    const bool last_of_seq = cur.b + 1 == cur.nb;
+    const int nvalid = last_of_seq ? cur.s_len - cur.b * kBlockSize : kBlockSize;
+    if (nvalid < kBlockSize)
+      block_update<T, G, true>(st, qreg, kx, vx, scale2, row, nvalid);
+    else
+      block_update<T, G, false>(st, qreg, kx, vx, scale2, row, kBlockSize);
+    if (!(last_of_seq || last_of_range)) return;
 
     // merge the four 16-lane rows (lanes l, l^16, l^32, l^48 hold the same dims)
 #pragma unroll
@@ -236,19 +287,19 @@ __global__ __launch_bounds__(kWave) void decode_attend_kernel(
         st.m[g] = m_n;
       }
     }
-
+    const bool whole = piece_lo == 0 && last_of_seq;     // the piece is the entire sequence
     if (row == 0) {
 #pragma unroll
       for (int g = 0; g < G; ++g) {
-        const int h = kvh * G + g;
-        if (n_chunks == 1) {
+        if (whole) {
           const float inv = 1.f / st.l[g];
           u32x4 o;
 #pragma unroll
           for (int w2 = 0; w2 < 4; ++w2) o[w2] = pack2<T>(st.acc[g][2 * w2] * inv, st.acc[g][2 * w2 + 1] * inv);
-          *reinterpret_cast<u32x4*>(out + ((size_t)r * num_q_heads + h) * kHeadDim + sub * 8) = o;
+          *reinterpret_cast<u32x4*>(out + ((size_t)cur.r * num_q_heads + cur.h * G + g) * kHeadDim + sub * 8) = o;
         } else {
-          const size_t pi = (size_t)slot * num_q_heads + h;
+          // slot 0: the piece cut at the start of this wave's range; slot 1: the one cut at its end
+          const size_t pi = ((size_t)wave * 2 + (piece_lo == 0 ? 1 : 0)) * G + g;
           float4* dst = reinterpret_cast<float4*>(part_acc + pi * kPartialFloats + sub * 8);
           dst[0] = make_float4(st.acc[g][0], st.acc[g][1], st.acc[g][2], st.acc[g][3]);
           dst[1] = make_float4(st.acc[g][4], st.acc[g][5], st.acc[g][6], st.acc[g][7]);
@@ -256,34 +307,73 @@ __global__ __launch_bounds__(kWave) void decode_attend_kernel(
         }
       }
     }
+    if (!last_of_range) {                   // a new (r, h) starts with the next block
+      st.reset();
+      piece_lo = 0;
+#pragma unroll
+      for (int g = 0; g < G; ++g) qreg[g] = qnext[g];
+    }
+  };
+
+  int i = 0;
+  while (true) {
+    // -- even step: consume from (ka, va), prefetch into (kb, vb)
+    if (i + 1 < n_blocks) {
+      if (nxt.b == 0) load_q(qnext, nxt);
+      load_tile(kb, k_cache + nxt.off, lane);
+      load_tile(vb, v_cache + nxt.off, lane);
+    }
+    consume(ka, va, i + 1 == n_blocks);
+    if (++i == n_blocks) break;
+    cur = nxt;
+    nxt = far;
+    if (i + 2 < n_blocks) step(far);
+    // -- odd step: consume from (kb, vb), prefetch into (ka, va)
+    if (i + 1 < n_blocks) {
+      if (nxt.b == 0) load_q(qnext, nxt);
+      load_tile(ka, k_cache + nxt.off, lane);
+      load_tile(va, v_cache + nxt.off, lane);
+    }
+    consume(kb, vb, i + 1 == n_blocks);
+    if (++i == n_blocks) break;
+    cur = nxt;
+    nxt = far;
+    if (i + 2 < n_blocks) step(far);
   }
 }
 
 // ----------------------------------------------------------------- merge ----
 template <typename T>
-__global__ __launch_bounds__(kWave) void decode_merge_kernel(const int32_t* __restrict__ seq_lens,
-                                                             const int32_t* __restrict__ chunk_start,
+__global__ __launch_bounds__(kWave) void decode_merge_kernel(const DecodeHeader* __restrict__ header,
+                                                             const int32_t* __restrict__ seg_prefix,
                                                              const float2* __restrict__ part_ml,
                                                              const float* __restrict__ part_acc,
                                                              uint16_t* __restrict__ out, int32_t num_q_heads,
-                                                             int32_t max_tokens) {
+                                                             int32_t num_kv_heads) {
   const int r = blockIdx.x;
   const int h = blockIdx.y;
   const int lane = threadIdx.x;                          // dims 2*lane, 2*lane+1
-  const int s_len = min(seq_lens[r], max_tokens);
-  const int n_chunks = (s_len + kChunkTokens - 1) / kChunkTokens;
-  if (n_chunks == 1) return;                             // written directly by the attend kernel
+  const int group = num_q_heads / num_kv_heads;
+  const int nb = seg_prefix[r + 1] - seg_prefix[r];
   uint32_t* dst = reinterpret_cast<uint32_t*>(out + ((size_t)r * num_q_heads + h) * kHeadDim) + lane;
-  if (n_chunks <= 0) {
+  if (nb <= 0) {
     *dst = 0u;
     return;
   }
-  const size_t first = (size_t)chunk_start[r] * num_q_heads + h;
+  const long long gtot = header->gtot;
+  const int waves = header->waves;
+  const long long g0 = (long long)seg_prefix[r] * num_kv_heads + (long long)(h / group) * nb;
+  const int w_first = wave_of(gtot, waves, g0);
+  const int w_last = wave_of(gtot, waves, g0 + nb - 1);
+  if (w_first == w_last) return;                         // one wave saw the whole sequence and wrote the output
   float m = -INFINITY;
-  for (int c = 0; c < n_chunks; ++c) m = fmaxf(m, part_ml[first + (size_t)c * num_q_heads].x);
+  for (int w = w_first; w <= w_last; ++w) {
+    const size_t pi = ((size_t)w * 2 + (range_start(gtot, waves, w) > g0 ? 0 : 1)) * group + h % group;
+    m = fmaxf(m, part_ml[pi].x);
+  }
   float l = 0.f, a0 = 0.f, a1 = 0.f;
-  for (int c = 0; c < n_chunks; ++c) {
-    const size_t pi = first + (size_t)c * num_q_heads;
+  for (int w = w_first; w <= w_last; ++w) {
+    const size_t pi = ((size_t)w * 2 + (range_start(gtot, waves, w) > g0 ? 0 : 1)) * group + h % group;
     const float2 ml = part_ml[pi];
     const float wgt = fast_exp2(ml.x - m);
     const float2 a = *reinterpret_cast<const float2*>(part_acc + pi * kPartialFloats + 2 * lane);
@@ -302,29 +392,35 @@ static int launch_typed(const vtc_attn_params& p, int32_t num_seqs, const void* 
                         void* workspace, hipStream_t stream, hipEvent_t ev_begin, hipEvent_t ev_end) {
   const DecodeWorkspace ws = decode_workspace_layout(p, num_seqs, 0);
   char* base = static_cast<char*>(workspace);
-  int32_t* chunk_start = reinterpret_cast<int32_t*>(base + ws.chunk_start_off);
-  int2* items = reinterpret_cast<int2*>(base + ws.items_off);
+  DecodeHeader* header = reinterpret_cast<DecodeHeader*>(base + ws.header_off);
+  int32_t* seg_prefix = reinterpret_cast<int32_t*>(base + ws.seg_prefix_off);
+  int4* wave_desc = reinterpret_cast<int4*>(base + ws.wave_desc_off);
   float2* part_ml = reinterpret_cast<float2*>(base + ws.ml_off);
   float* part_acc = reinterpret_cast<float*>(base + ws.acc_off);
   const int32_t max_tokens = p.max_blocks_per_seq * kBlockSize;
 
-  hipLaunchKernelGGL(decode_plan_kernel, dim3(1), dim3(kPlanThreads), 0, stream, seq_lens, num_seqs, max_tokens,
-                     chunk_start, items);
+  // Grid = the waves the chip holds at once (never more, so no wave waits for a slot while
+  // the others are already half way through their share).
+  static int waves_per_cu = 0;
+  if (waves_per_cu == 0) {
+    int occ = 0;
+    if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&occ, decode_attend_kernel<T, G>, kWave, 0) != hipSuccess || occ <= 0)
+      occ = 8;
+    waves_per_cu = occ < VTC_DECODE_WAVES_PER_CU ? occ : VTC_DECODE_WAVES_PER_CU;
+  }
+  long long resident = (long long)device_cu_count() * waves_per_cu;
+  const int grid = (int)(resident < kMaxDecodeWaves ? resident : kMaxDecodeWaves);
 
-  const long long max_work = ws.max_items * p.num_kv_heads;
-  if (max_work >= (1ll << 31)) return VTC_ERR_UNSUPPORTED;
-  const long long resident = (long long)device_cu_count() * 16;      // waves the chip can hold at once
-  const int grid = (int)(max_work < resident ? (max_work < 1 ? 1 : max_work) : resident);
+  hipLaunchKernelGGL(decode_plan_kernel, dim3(1), dim3(kPlanThreads), 0, stream, seq_lens, num_seqs, p.num_kv_heads,
+                     max_tokens, grid, header, seg_prefix, wave_desc);
   if (ev_begin && hipEventRecord(ev_begin, stream) != hipSuccess) return VTC_ERR_HIP;
   hipLaunchKernelGGL((decode_attend_kernel<T, G>), dim3(grid), dim3(kWave), 0, stream,
                      static_cast<const uint16_t*>(q), static_cast<const uint16_t*>(k_cache),
                      static_cast<const uint16_t*>(v_cache), block_table, seq_lens, static_cast<uint16_t*>(out),
-                     chunk_start, items, part_ml, part_acc, num_seqs, p.num_kv_heads, p.max_blocks_per_seq,
-                     p.scale * kLog2e);
+                     wave_desc, part_ml, part_acc, p.num_kv_heads, p.max_blocks_per_seq, p.scale * kLog2e);
   if (ev_end && hipEventRecord(ev_end, stream) != hipSuccess) return VTC_ERR_HIP;
-
-  hipLaunchKernelGGL((decode_merge_kernel<T>), dim3(num_seqs, p.num_q_heads), dim3(kWave), 0, stream, seq_lens,
-                     chunk_start, part_ml, part_acc, static_cast<uint16_t*>(out), p.num_q_heads, max_tokens);
+  hipLaunchKernelGGL((decode_merge_kernel<T>), dim3(num_seqs, p.num_q_heads), dim3(kWave), 0, stream, header,
+                     seg_prefix, part_ml, part_acc, static_cast<uint16_t*>(out), p.num_q_heads, p.num_kv_heads);
   return hipGetLastError() == hipSuccess ? VTC_OK : VTC_ERR_HIP;
 }
 
@@ -344,7 +440,9 @@ static int launch_group(const vtc_attn_params& p, int32_t num_seqs, const void* 
 int launch_decode(const vtc_attn_params& p, int32_t num_seqs, const void* q, const void* k_cache,
                   const void* v_cache, const int32_t* block_table, const int32_t* seq_lens, void* out,
                   void* workspace, hipStream_t stream, hipEvent_t ev_begin, hipEvent_t ev_end) {
-  if (num_seqs > 65535 * 1024) return VTC_ERR_UNSUPPORTED;
+  // the flattened block index must fit the 64-bit products used above and the grid limits of the merge launch
+  if ((long long)num_seqs * p.max_blocks_per_seq >= (1ll << 31)) return VTC_ERR_UNSUPPORTED;
+  if (p.num_q_heads > 65535) return VTC_ERR_UNSUPPORTED;
   if (p.dtype == VTC_F16)
     return launch_group<F16>(p, num_seqs, q, k_cache, v_cache, block_table, seq_lens, out, workspace, stream, ev_begin, ev_end);
   return launch_group<BF16>(p, num_seqs, q, k_cache, v_cache, block_table, seq_lens, out, workspace, stream, ev_begin, ev_end);

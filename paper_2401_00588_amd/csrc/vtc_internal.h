@@ -15,13 +15,30 @@ constexpr int kWave = 64;           // CDNA wavefront
 constexpr int kTileElems = kBlockSize * kHeadDim;   // elements of one (block, kv head) K or V tile
 constexpr float kLog2e = 1.4426950408889634f;
 
-// Split of a context into work items for decode attention: each item covers
-// kChunkTokens consecutive tokens of one (sequence, kv head).
-constexpr int kChunkTokens = 256;
-constexpr int kChunkBlocks = kChunkTokens / kBlockSize;
+// Build-time tunables of the decode kernel (override with -D for experiments).
+#ifndef VTC_DECODE_WAVES_PER_CU
+#define VTC_DECODE_WAVES_PER_CU 16       // waves launched per compute unit (capped by occupancy)
+#endif
+#ifndef VTC_DECODE_NT_LOADS
+#define VTC_DECODE_NT_LOADS 1            // 1: stream K/V with non-temporal loads
+#endif
+#ifndef VTC_DECODE_MIN_BLOCKS_PER_WAVE
+#define VTC_DECODE_MIN_BLOCKS_PER_WAVE 2 // small batches use fewer waves rather than shorter ranges
+#endif
 
-// One fp32 partial result of a chunk: running max m (log2 domain), sum l, acc[128].
+// Decode attention cuts the batch's stream of KV blocks into one range per wave.
+constexpr int kMaxDecodeWaves = 8192;                          // upper bound on the launch, sizes the workspace
+constexpr int kMinBlocksPerWave = VTC_DECODE_MIN_BLOCKS_PER_WAVE;
+
+// One fp32 partial result of a piece: running max m (log2 domain), sum l, acc[128].
 constexpr int kPartialFloats = kHeadDim;
+
+// Written by the planning kernel, read by the merge kernel.
+struct DecodeHeader {
+  long long gtot;   // KV blocks in the stream: (sum over sequences of blocks) * num_kv_heads
+  int waves;        // waves that received a non-empty range
+  int pad;
+};
 
 using u32x4 = uint32_t __attribute__((ext_vector_type(4)));
 using f16x2 = _Float16 __attribute__((ext_vector_type(2)));
@@ -101,30 +118,32 @@ __device__ __forceinline__ float fast_exp2(float x) { return __builtin_amdgcn_ex
 
 // ---- host side --------------------------------------------------------------
 struct DecodeWorkspace {
-  size_t chunk_start_off;   // int32 [num_seqs + 1]   exclusive prefix of chunks per sequence
-  size_t items_off;         // int2  [max_items]      (sequence, chunk index)
-  size_t ml_off;            // float2[max_items * Hq] (m, l) per partial
-  size_t acc_off;           // float [max_items * Hq * 128]
+  size_t header_off;        // DecodeHeader
+  size_t seg_prefix_off;    // int32 [num_seqs + 1]          exclusive prefix of KV blocks per sequence
+  size_t wave_desc_off;     // int4  [kMaxDecodeWaves]       (r, h, b, n_blocks): start and length of a wave's range
+  size_t ml_off;            // float2[2 * kMaxDecodeWaves * G] (m, l) of each partial piece
+  size_t acc_off;           // float [2 * kMaxDecodeWaves * G * 128]
   size_t total_bytes;
-  int64_t max_items;
 };
 
 inline size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
 
-inline DecodeWorkspace decode_workspace_layout(const vtc_attn_params& p, int32_t num_seqs, int32_t max_seq_len) {
-  const int64_t cap = (int64_t)p.max_blocks_per_seq * p.block_size;
-  int64_t s = (max_seq_len <= 0 || max_seq_len > cap) ? cap : max_seq_len;
+// The footprint depends on the number of sequences and on Hq/Hkv only: a wave owns at most
+// two partial pieces however long the contexts are.
+inline DecodeWorkspace decode_workspace_layout(const vtc_attn_params& p, int32_t num_seqs, int32_t /*max_seq_len*/) {
+  const size_t group = (size_t)(p.num_q_heads / p.num_kv_heads);
   DecodeWorkspace w{};
-  w.max_items = (int64_t)num_seqs * ((s + kChunkTokens - 1) / kChunkTokens);
   size_t at = 0;
-  w.chunk_start_off = at;
+  w.header_off = at;
+  at = 256;
+  w.seg_prefix_off = at;
   at = align_up(at + sizeof(int32_t) * ((size_t)num_seqs + 1), 256);
-  w.items_off = at;
-  at = align_up(at + sizeof(int32_t) * 2 * (size_t)w.max_items, 256);
+  w.wave_desc_off = at;
+  at = align_up(at + sizeof(int32_t) * 4 * (size_t)kMaxDecodeWaves, 256);
   w.ml_off = at;
-  at = align_up(at + sizeof(float) * 2 * (size_t)w.max_items * p.num_q_heads, 256);
+  at = align_up(at + sizeof(float) * 2 * 2 * (size_t)kMaxDecodeWaves * group, 256);
   w.acc_off = at;
-  at = align_up(at + sizeof(float) * kPartialFloats * (size_t)w.max_items * p.num_q_heads, 256);
+  at = align_up(at + sizeof(float) * kPartialFloats * 2 * (size_t)kMaxDecodeWaves * group, 256);
   w.total_bytes = at;
   return w;
 }
