@@ -16,9 +16,9 @@
 //           either the final output (the piece is the whole sequence) or an fp32
 //           partial (m, l, acc[128] per q head).  A wave owns at most two partial
 //           pieces: one cut at its range start and one cut at its range end.
-//   merge   one wave per (r, q head): finds the waves whose ranges overlap the
-//           sequence, combines their partials exactly (rescale by exp2(m_c - m))
-//           and writes the output; writes zeros for empty sequences.
+//   merge   one wave per range boundary: if the boundary cuts a (r, h), combines the
+//           partials of the waves that share it exactly (rescale by exp2(m_c - m))
+//           and writes the output; also writes zeros for empty sequences.
 //
 // Lane mapping inside a wave: lane = 16 * row + sub.  A 16-byte load instruction
 // covers 4 tokens x 128 dims: row picks the token (4 * i + row for load i of a
@@ -32,70 +32,94 @@ namespace vtc {
 
 constexpr int kPlanThreads = 1024;
 
-// 64-bit helpers shared by plan and merge: start of wave w's range, and the wave that owns block g.
-__device__ __forceinline__ long long range_start(long long gtot, int waves, int w) {
-  return gtot * (long long)w / (long long)waves;
-}
-__device__ __forceinline__ int wave_of(long long gtot, int waves, long long g) {
-  int w = (int)(g * (long long)waves / gtot);
-  if (w + 1 < waves && range_start(gtot, waves, w + 1) <= g) ++w;
-  return w;
-}
+// Start of wave w's range in the stream, floor(gtot * w / waves), from quot = gtot / waves and
+// rem = gtot % waves (rem * w < 2^26 because waves <= kMaxDecodeWaves): no 64-bit division.
+struct RangeMap {
+  long long quot;
+  uint32_t rem;
+  uint32_t waves;
+  __device__ __forceinline__ long long start(int w) const {
+    return quot * (long long)w + (long long)(rem * (uint32_t)w / waves);
+  }
+};
 
 // ------------------------------------------------------------------ plan ----
+constexpr int kPlanLdsSeqs = 8192;     // sequences whose block prefix is also kept in LDS for the range search
+
 __global__ __launch_bounds__(kPlanThreads) void decode_plan_kernel(const int32_t* __restrict__ seq_lens,
                                                                    int32_t num_seqs, int32_t num_kv_heads,
                                                                    int32_t max_tokens, int32_t max_waves,
                                                                    DecodeHeader* __restrict__ header,
                                                                    int32_t* __restrict__ seg_prefix,
                                                                    int4* __restrict__ wave_desc) {
-  __shared__ int32_t scan[kPlanThreads];
+  __shared__ int32_t prefix_lds[kPlanLdsSeqs + 1];
+  __shared__ int32_t wave_sums[kPlanThreads / kWave];
   __shared__ int32_t carry;
-  if (threadIdx.x == 0) carry = 0;
+  const int tid = threadIdx.x;
+  const int lane = tid & (kWave - 1);
+  const int wid = tid / kWave;
+  if (tid == 0) carry = 0;
   __syncthreads();
   for (int base = 0; base < num_seqs; base += kPlanThreads) {
-    const int r = base + (int)threadIdx.x;
+    const int r = base + tid;
     int32_t n = 0;
     if (r < num_seqs) n = (min(max(seq_lens[r], 0), max_tokens) + kBlockSize - 1) / kBlockSize;
-    scan[threadIdx.x] = n;
-    __syncthreads();
-    for (int off = 1; off < kPlanThreads; off <<= 1) {     // inclusive Hillis-Steele scan
-      int32_t v = (int)threadIdx.x >= off ? scan[threadIdx.x - off] : 0;
-      __syncthreads();
-      scan[threadIdx.x] += v;
-      __syncthreads();
+    // inclusive scan inside the wave, then across the 16 waves
+    int32_t x = n;
+#pragma unroll
+    for (int off = 1; off < kWave; off <<= 1) {
+      const int32_t y = __shfl_up(x, off);
+      if (lane >= off) x += y;
     }
-    if (r < num_seqs) seg_prefix[r] = carry + scan[threadIdx.x] - n;
+    if (lane == kWave - 1) wave_sums[wid] = x;
     __syncthreads();
-    if (threadIdx.x == kPlanThreads - 1) carry += scan[threadIdx.x];
+    int32_t before = carry;
+    for (int j = 0; j < wid; ++j) before += wave_sums[j];
+    if (r < num_seqs) {
+      const int32_t excl = before + x - n;
+      seg_prefix[r] = excl;
+      if (r < kPlanLdsSeqs) prefix_lds[r] = excl;
+    }
+    __syncthreads();
+    if (tid == kPlanThreads - 1) carry = before + x;
     __syncthreads();
   }
   const int32_t total_blocks = carry;
-  if (threadIdx.x == 0) seg_prefix[num_seqs] = total_blocks;
+  if (tid == 0) {
+    seg_prefix[num_seqs] = total_blocks;
+    if (num_seqs <= kPlanLdsSeqs) prefix_lds[num_seqs] = total_blocks;
+  }
   const long long gtot = (long long)total_blocks * num_kv_heads;
   // every active wave gets at least kMinBlocksPerWave blocks
   const long long want = (gtot + kMinBlocksPerWave - 1) / kMinBlocksPerWave;
   const int waves = (int)(want < (long long)max_waves ? want : (long long)max_waves);
-  if (threadIdx.x == 0) {
+  RangeMap map{0, 0u, 1u};
+  if (waves > 0) map = RangeMap{gtot / waves, (uint32_t)(gtot % waves), (uint32_t)waves};
+  if (tid == 0) {
     header->gtot = gtot;
+    header->quot = map.quot;
+    header->rem = (int)map.rem;
     header->waves = waves;
   }
-  __threadfence();
-  __syncthreads();                                           // seg_prefix is complete and visible
-  for (int w = threadIdx.x; w < max_waves; w += kPlanThreads) {
+  __syncthreads();                                           // the prefix is complete and visible to the workgroup
+  const bool in_lds = num_seqs <= kPlanLdsSeqs;
+  for (int w = tid; w < max_waves; w += kPlanThreads) {
     int4 d = make_int4(0, 0, 0, 0);
     if (w < waves) {
-      const long long g = range_start(gtot, waves, w);
-      const long long n = range_start(gtot, waves, w + 1) - g;
-      // the sequence r with seg_prefix[r] * Hkv <= g < seg_prefix[r+1] * Hkv
+      const long long g = map.start(w);
+      const long long n = map.start(w + 1) - g;
+      // the sequence r with prefix[r] * Hkv <= g < prefix[r+1] * Hkv
       int lo = 0, hi = num_seqs - 1;
       while (lo < hi) {
         const int mid = (lo + hi) >> 1;
-        if ((long long)seg_prefix[mid + 1] * num_kv_heads > g) hi = mid; else lo = mid + 1;
+        const int32_t pm = in_lds ? prefix_lds[mid + 1] : seg_prefix[mid + 1];
+        if ((long long)pm * num_kv_heads > g) hi = mid; else lo = mid + 1;
       }
-      const int nb = seg_prefix[lo + 1] - seg_prefix[lo];
-      const long long off = g - (long long)seg_prefix[lo] * num_kv_heads;
-      d = make_int4(lo, (int)(off / nb), (int)(off % nb), (int)n);
+      const int32_t p0 = in_lds ? prefix_lds[lo] : seg_prefix[lo];
+      const int32_t p1 = in_lds ? prefix_lds[lo + 1] : seg_prefix[lo + 1];
+      const int nb = p1 - p0;
+      const uint32_t off = (uint32_t)(g - (long long)p0 * num_kv_heads);   // < nb * Hkv < 2^31
+      d = make_int4(lo, (int)(off / (uint32_t)nb), (int)(off % (uint32_t)nb), (int)n);
     }
     wave_desc[w] = d;
   }
@@ -174,14 +198,16 @@ __device__ __forceinline__ void block_update(RowState<G>& st, const u32x4 (&q)[G
   }
 }
 
-__device__ __forceinline__ void load_tile(u32x4 (&dst)[4], const uint16_t* __restrict__ tile, int lane) {
+// Load one 4 KiB tile (4 x 1 KiB across the wave).  `stride16` is kWave for a real tile; 0 turns the
+// four loads into re-reads of one 1 KiB line set (the throw-away prefetch at the end of a range).
+__device__ __forceinline__ void load_tile(u32x4 (&dst)[4], const uint16_t* __restrict__ tile, int lane, int stride16) {
   const u32x4* src = reinterpret_cast<const u32x4*>(tile) + lane;
 #pragma unroll
   for (int i = 0; i < 4; ++i) {
 #if VTC_DECODE_NT_LOADS
-    dst[i] = __builtin_nontemporal_load(src + i * kWave);     // streamed once: keep it out of the caches' way
+    dst[i] = __builtin_nontemporal_load(src + i * stride16);  // streamed once: keep it out of the caches' way
 #else
-    dst[i] = src[i * kWave];
+    dst[i] = src[i * stride16];
 #endif
   }
 }
@@ -206,7 +232,10 @@ __global__ __launch_bounds__(kWave) void decode_attend_kernel(
   const int num_q_heads = num_kv_heads * G;
   const int max_tokens = max_blocks_per_seq * kBlockSize;
   const int wave = blockIdx.x;
-  const int4 desc = wave_desc[wave];
+  const int4 desc_v = wave_desc[wave];
+  // the descriptor is the same for all lanes: keep it (and everything derived from it) in scalar registers
+  const int4 desc = make_int4(__builtin_amdgcn_readfirstlane(desc_v.x), __builtin_amdgcn_readfirstlane(desc_v.y),
+                              __builtin_amdgcn_readfirstlane(desc_v.z), __builtin_amdgcn_readfirstlane(desc_v.w));
   const int n_blocks = desc.w;
   if (n_blocks <= 0) return;
   const size_t block_stride = (size_t)num_kv_heads * kTileElems;
@@ -250,18 +279,21 @@ __global__ __launch_bounds__(kWave) void decode_attend_kernel(
   }
   if (n_blocks > 2) step(far);
 
-  u32x4 qreg[G], qnext[G];
-  load_q(qreg, cur);
   RowState<G> st;
   st.reset();
   int piece_lo = cur.b;                    // first block of the current piece
 
-  u32x4 ka[4], va[4], kb[4], vb[4];
-  load_tile(ka, k_cache + cur.off, lane);
-  load_tile(va, v_cache + cur.off, lane);
+  // Two register sets (q, K tile, V tile), used alternately.  The q rows travel with the
+  // tiles, so a set always holds the query of the block it holds.
+  u32x4 qa[G], ka[4], va[4], qb[G], kb[4], vb[4];
+  load_q(qa, cur);
+  load_tile(ka, k_cache + cur.off, lane, kWave);
+  load_tile(va, v_cache + cur.off, lane, kWave);
+  // where the prefetch goes when there is no next block: 1 KiB of the (cache-resident) range table
+  const uint16_t* const dummy = reinterpret_cast<const uint16_t*>(wave_desc);
 
-  // Consume the block at `cur` from (kx, vx); close the piece if it ends here.
-  auto consume = [&](u32x4 (&kx)[4], u32x4 (&vx)[4], bool last_of_range) {
+  // Consume the block at `cur` from (qreg, kx, vx); close the piece if it ends here.
+  auto consume = [&](const u32x4 (&qreg)[G], u32x4 (&kx)[4], u32x4 (&vx)[4], bool last_of_range) {
     const bool last_of_seq = cur.b + 1 == cur.nb;
     const int nvalid = last_of_seq ? cur.s_len - cur.b * kBlockSize : kBlockSize;
     if (nvalid < kBlockSize)
@@ -307,34 +339,37 @@ __global__ __launch_bounds__(kWave) void decode_attend_kernel(
         }
       }
     }
-    if (!last_of_range) {                   // a new (r, h) starts with the next block
-      st.reset();
-      piece_lo = 0;
-#pragma unroll
-      for (int g = 0; g < G; ++g) qreg[g] = qnext[g];
-    }
+    st.reset();                             // a new (r, h) starts with the next block
+    piece_lo = 0;
   };
 
+  // The prefetch of the next block is unconditional (no branch around the loads, so the
+  // hardware load counter stays exact and a tile's wait never covers the loads issued after
+  // it).  On the last block of the range it is pointed at 1 KiB that is already in cache and
+  // its result is dropped.  q is re-read with every block for the same reason (a 256-byte
+  // row that stays in cache); it only changes when the next block starts a new (r, h).
   int i = 0;
   while (true) {
-    // -- even step: consume from (ka, va), prefetch into (kb, vb)
-    if (i + 1 < n_blocks) {
-      if (nxt.b == 0) load_q(qnext, nxt);
-      load_tile(kb, k_cache + nxt.off, lane);
-      load_tile(vb, v_cache + nxt.off, lane);
+    // -- even step: consume set a, prefetch into set b
+    {
+      const bool more = i + 1 < n_blocks;
+      load_q(qb, nxt);
+      load_tile(kb, more ? k_cache + nxt.off : dummy, lane, more ? kWave : 0);
+      load_tile(vb, more ? v_cache + nxt.off : dummy, lane, more ? kWave : 0);
     }
-    consume(ka, va, i + 1 == n_blocks);
+    consume(qa, ka, va, i + 1 == n_blocks);
     if (++i == n_blocks) break;
     cur = nxt;
     nxt = far;
     if (i + 2 < n_blocks) step(far);
-    // -- odd step: consume from (kb, vb), prefetch into (ka, va)
-    if (i + 1 < n_blocks) {
-      if (nxt.b == 0) load_q(qnext, nxt);
-      load_tile(ka, k_cache + nxt.off, lane);
-      load_tile(va, v_cache + nxt.off, lane);
+    // -- odd step: consume set b, prefetch into set a
+    {
+      const bool more = i + 1 < n_blocks;
+      load_q(qa, nxt);
+      load_tile(ka, more ? k_cache + nxt.off : dummy, lane, more ? kWave : 0);
+      load_tile(va, more ? v_cache + nxt.off : dummy, lane, more ? kWave : 0);
     }
-    consume(kb, vb, i + 1 == n_blocks);
+    consume(qb, kb, vb, i + 1 == n_blocks);
     if (++i == n_blocks) break;
     cur = nxt;
     nxt = far;
@@ -343,46 +378,61 @@ __global__ __launch_bounds__(kWave) void decode_attend_kernel(
 }
 
 // ----------------------------------------------------------------- merge ----
+// Only a sequence-head that a range boundary cuts needs merging, so the merge is driven by the
+// boundaries: block w looks at the cut between waves w-1 and w.  If that cut falls inside a
+// (r, kv head) and wave w-1 holds its beginning, the block combines the pieces of waves
+// w-1, w, w+1, ... for one of the G query heads of that kv head (blockIdx.y).  Blocks past the
+// waves zero the output rows of empty sequences.
 template <typename T>
 __global__ __launch_bounds__(kWave) void decode_merge_kernel(const DecodeHeader* __restrict__ header,
                                                              const int32_t* __restrict__ seg_prefix,
+                                                             const int4* __restrict__ wave_desc,
                                                              const float2* __restrict__ part_ml,
                                                              const float* __restrict__ part_acc,
-                                                             uint16_t* __restrict__ out, int32_t num_q_heads,
-                                                             int32_t num_kv_heads) {
-  const int r = blockIdx.x;
-  const int h = blockIdx.y;
+                                                             uint16_t* __restrict__ out, int32_t num_seqs,
+                                                             int32_t num_q_heads, int32_t num_kv_heads,
+                                                             int32_t max_waves) {
   const int lane = threadIdx.x;                          // dims 2*lane, 2*lane+1
   const int group = num_q_heads / num_kv_heads;
-  const int nb = seg_prefix[r + 1] - seg_prefix[r];
-  uint32_t* dst = reinterpret_cast<uint32_t*>(out + ((size_t)r * num_q_heads + h) * kHeadDim) + lane;
-  if (nb <= 0) {
-    *dst = 0u;
+  const int g = blockIdx.y;                              // query head inside the group
+  if ((int)blockIdx.x >= max_waves) {                    // empty sequences: all-zero rows
+    const int r = blockIdx.x - max_waves;
+    if (g != 0 || seg_prefix[r + 1] - seg_prefix[r] > 0) return;
+    uint32_t* dst = reinterpret_cast<uint32_t*>(out + (size_t)r * num_q_heads * kHeadDim);
+    for (int i = lane; i < num_q_heads * (kHeadDim / 2); i += kWave) dst[i] = 0u;
     return;
   }
-  const long long gtot = header->gtot;
+  const int w = blockIdx.x;
   const int waves = header->waves;
-  const long long g0 = (long long)seg_prefix[r] * num_kv_heads + (long long)(h / group) * nb;
-  const int w_first = wave_of(gtot, waves, g0);
-  const int w_last = wave_of(gtot, waves, g0 + nb - 1);
-  if (w_first == w_last) return;                         // one wave saw the whole sequence and wrote the output
-  float m = -INFINITY;
-  for (int w = w_first; w <= w_last; ++w) {
-    const size_t pi = ((size_t)w * 2 + (range_start(gtot, waves, w) > g0 ? 0 : 1)) * group + h % group;
-    m = fmaxf(m, part_ml[pi].x);
+  if (w == 0 || w >= waves) return;
+  const int4 d = wave_desc[w];                           // (r, kv head, block) where wave w starts
+  if (d.z == 0) return;                                  // the cut coincides with a sequence-head boundary
+  if (d.z > wave_desc[w - 1].w) return;                  // the beginning lies before wave w-1: an earlier block merges it
+  const int nb = seg_prefix[d.x + 1] - seg_prefix[d.x];
+  const RangeMap map{header->quot, (uint32_t)header->rem, (uint32_t)waves};
+  const long long g1 = map.start(w) + (nb - d.z);         // end of the sequence-head in the stream
+  {
+    // wave w-1 holds the beginning (its slot 1); waves w.. hold continuations (their slot 0)
+    float m = part_ml[((size_t)(w - 1) * 2 + 1) * group + g].x;
+    int w_end = w;
+    while (w_end < waves && map.start(w_end) < g1) {
+      m = fmaxf(m, part_ml[((size_t)w_end * 2) * group + g].x);
+      ++w_end;
+    }
+    float l = 0.f, a0 = 0.f, a1 = 0.f;
+    for (int j = w - 1; j < w_end; ++j) {
+      const size_t pi = ((size_t)j * 2 + (j == w - 1 ? 1 : 0)) * group + g;
+      const float2 ml = part_ml[pi];
+      const float wgt = fast_exp2(ml.x - m);
+      const float2 a = *reinterpret_cast<const float2*>(part_acc + pi * kPartialFloats + 2 * lane);
+      l = fmaf(ml.y, wgt, l);
+      a0 = fmaf(a.x, wgt, a0);
+      a1 = fmaf(a.y, wgt, a1);
+    }
+    const float inv = 1.f / l;
+    uint32_t* dst = reinterpret_cast<uint32_t*>(out + ((size_t)d.x * num_q_heads + d.y * group + g) * kHeadDim) + lane;
+    *dst = pack2<T>(a0 * inv, a1 * inv);
   }
-  float l = 0.f, a0 = 0.f, a1 = 0.f;
-  for (int w = w_first; w <= w_last; ++w) {
-    const size_t pi = ((size_t)w * 2 + (range_start(gtot, waves, w) > g0 ? 0 : 1)) * group + h % group;
-    const float2 ml = part_ml[pi];
-    const float wgt = fast_exp2(ml.x - m);
-    const float2 a = *reinterpret_cast<const float2*>(part_acc + pi * kPartialFloats + 2 * lane);
-    l = fmaf(ml.y, wgt, l);
-    a0 = fmaf(a.x, wgt, a0);
-    a1 = fmaf(a.y, wgt, a1);
-  }
-  const float inv = 1.f / l;
-  *dst = pack2<T>(a0 * inv, a1 * inv);
 }
 
 // -------------------------------------------------------------- launcher ----
@@ -419,8 +469,9 @@ static int launch_typed(const vtc_attn_params& p, int32_t num_seqs, const void* 
                      static_cast<const uint16_t*>(v_cache), block_table, seq_lens, static_cast<uint16_t*>(out),
                      wave_desc, part_ml, part_acc, p.num_kv_heads, p.max_blocks_per_seq, p.scale * kLog2e);
   if (ev_end && hipEventRecord(ev_end, stream) != hipSuccess) return VTC_ERR_HIP;
-  hipLaunchKernelGGL((decode_merge_kernel<T>), dim3(num_seqs, p.num_q_heads), dim3(kWave), 0, stream, header,
-                     seg_prefix, part_ml, part_acc, static_cast<uint16_t*>(out), p.num_q_heads, p.num_kv_heads);
+  hipLaunchKernelGGL((decode_merge_kernel<T>), dim3(grid + num_seqs, G), dim3(kWave), 0, stream, header, seg_prefix,
+                     wave_desc, part_ml, part_acc, static_cast<uint16_t*>(out), num_seqs, p.num_q_heads,
+                     p.num_kv_heads, grid);
   return hipGetLastError() == hipSuccess ? VTC_OK : VTC_ERR_HIP;
 }
 
@@ -442,7 +493,6 @@ int launch_decode(const vtc_attn_params& p, int32_t num_seqs, const void* q, con
                   void* workspace, hipStream_t stream, hipEvent_t ev_begin, hipEvent_t ev_end) {
   // the flattened block index must fit the 64-bit products used above and the grid limits of the merge launch
   if ((long long)num_seqs * p.max_blocks_per_seq >= (1ll << 31)) return VTC_ERR_UNSUPPORTED;
-  if (p.num_q_heads > 65535) return VTC_ERR_UNSUPPORTED;
   if (p.dtype == VTC_F16)
     return launch_group<F16>(p, num_seqs, q, k_cache, v_cache, block_table, seq_lens, out, workspace, stream, ev_begin, ev_end);
   return launch_group<BF16>(p, num_seqs, q, k_cache, v_cache, block_table, seq_lens, out, workspace, stream, ev_begin, ev_end);

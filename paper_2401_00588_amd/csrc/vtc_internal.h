@@ -36,8 +36,9 @@ constexpr int kPartialFloats = kHeadDim;
 // Written by the planning kernel, read by the merge kernel.
 struct DecodeHeader {
   long long gtot;   // KV blocks in the stream: (sum over sequences of blocks) * num_kv_heads
+  long long quot;   // gtot / waves
+  int rem;          // gtot % waves
   int waves;        // waves that received a non-empty range
-  int pad;
 };
 
 using u32x4 = uint32_t __attribute__((ext_vector_type(4)));

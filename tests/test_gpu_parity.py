@@ -137,6 +137,21 @@ def test_decode_ignores_rows_past_seq_len_and_handles_empty_sequences(torch, dty
     assert (got[0] == 0).all() and (got[4] == 0).all()
 
 
+@pytest.mark.parametrize("n,hq,hkv,dtype", [(2500, 4, 2, "bf16"), (9000, 2, 2, "f16")])
+def test_decode_many_short_sequences(torch, n, hq, hkv, dtype):
+    # more sequences than one planning pass (1024) and than the planner's on-chip prefix table (8192) hold;
+    # many ranges then span several whole sequences, some of them empty
+    say(f"decode {n} short sequences dtype={dtype}")
+    rng = np.random.default_rng(n)
+    seq = rng.integers(0, 49, size=n).astype(np.int32)
+    seq[rng.integers(0, n, size=5)] = 700          # a few long ones, cut by several range boundaries
+    got, want = _decode_case(torch, seq, hq, hkv, dtype, seed=n + 1)
+    err = np.abs(got - want).max()
+    say(f"  max abs err {err:.3e}")
+    assert np.isfinite(got).all() and err <= TOL[dtype]
+    assert (got[seq == 0] == 0).all()
+
+
 def test_decode_single_key_and_identical_keys(torch):
     say("decode closed forms on the GPU")
     rng = np.random.default_rng(33)
