@@ -2,208 +2,332 @@
 // (the attention part of forward_prefill(B_new), Algorithm 2 of the paper;
 // Section 2.1 describes prefilling as processing all prompt tokens at once).
 //
-// One workgroup (4 wavefronts) handles 64 consecutive chunk tokens of one
-// (sequence, q head); each wave owns 16 query rows.  The workgroup walks the
-// visible keys in tiles of 64, staging the K and V tiles of the head's KV group
-// in LDS.  Per tile and wave:
-//   S^T = K . Q^T      16 x v_mfma_f32_16x16x32  (A = K rows from LDS, B = Q^T in registers)
-//   online softmax     per query row (= per lane column), fp32, exp2 domain
-//   O^T += V^T . P^T   16 x v_mfma_f32_16x16x32  (A = V^T gathered from LDS, B = P^T)
-// Working with the transposed products makes the accumulator layout of S^T
-// (lane: query row l%16, keys 4*(l/16)+v) directly usable as the B operand of the
-// second product: the 8 contraction slots of lane group l/16 are assigned to keys
-// {4*(l/16)+v} of two neighbouring 16-key blocks, and V^T is gathered to match.
+// Work split.  A workgroup is 4 wavefronts; each wave owns 32 query rows, where a
+// row is a (chunk token, query head) pair.  All rows of a workgroup read the same
+// KV head, so with grouped-query attention the 4 waves take up to 4 query heads of
+// the group for the same 32 tokens (HW = heads per workgroup), and with HW < 4 the
+// remaining waves take further 32-token tiles.  The workgroup walks the keys it can
+// see in tiles of 64 and stages each K and V tile in LDS once for all 4 waves,
+// double-buffered: the global loads of tile j+1 are in flight while tile j is used.
+//
+// Per tile and wave, with v_mfma_f32_32x32x16 (A: 32 rows x 16, B: 16 x 32 columns):
+//   S^T = K . Q^T      2 key blocks x 8 steps over head_dim; A = 32 keys of the K tile
+//                      (16-byte LDS row reads), B = Q^T kept in registers
+//   online softmax     per query row = per lane column; fp32; exp2 domain
+//   O^T += V^T . P^T   A = V^T fragments: 4 consecutive keys at one dim per 8-byte
+//                      transposing LDS read (ds_read_b64_tr_b16) from the row-major
+//                      V tile; B = P^T, which is the accumulator layout of S^T as it
+//                      stands (lane: query row l%32, keys 8*(v/4) + 4*(l/32) + v%4)
+// The contraction slots of the second product are assigned to keys so that no data
+// moves between the two products: slots 0..3 of lane half hg are keys 16t+4hg+0..3
+// and slots 4..7 are keys 16t+8+4hg+0..3 of a 32-key block, for t = 0, 1.
 #include "vtc_internal.h"
 
 namespace vtc {
 
-using f32x4 = float __attribute__((ext_vector_type(4)));
+using f32x16 = float __attribute__((ext_vector_type(16)));
 using f16x8 = _Float16 __attribute__((ext_vector_type(8)));
 using bf16x8 = __bf16 __attribute__((ext_vector_type(8)));
+using s16x4 = short __attribute__((ext_vector_type(4)));
+using u32x2 = uint32_t __attribute__((ext_vector_type(2)));
 
-constexpr int kQTile = 64;          // query rows per workgroup
-constexpr int kKTile = 64;          // keys per LDS tile
-constexpr int kPitch = kHeadDim + 8;   // LDS row pitch in elements (272 B): conflict-free 16-byte row reads
-
-template <typename T>
-__device__ __forceinline__ f32x4 mfma16(u32x4 a, u32x4 b, f32x4 c);
-template <>
-__device__ __forceinline__ f32x4 mfma16<F16>(u32x4 a, u32x4 b, f32x4 c) {
-  return __builtin_amdgcn_mfma_f32_16x16x32_f16(__builtin_bit_cast(f16x8, a), __builtin_bit_cast(f16x8, b), c, 0, 0, 0);
-}
-template <>
-__device__ __forceinline__ f32x4 mfma16<BF16>(u32x4 a, u32x4 b, f32x4 c) {
-  return __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, a), __builtin_bit_cast(bf16x8, b), c, 0, 0, 0);
-}
+constexpr int kXcds = 8;                 // accelerator complex dies of an MI355X
+constexpr int kPfThreads = 256;
+constexpr int kPfRows = 32;              // query rows per wave
+constexpr int kPfKTile = 64;             // keys per LDS tile
+constexpr int kPitchK = kHeadDim + 8;    // 272 B rows: 16-byte reads of 16 consecutive rows hit all banks once
+constexpr int kPitchV = kHeadDim + 32;   // 320 B rows: the 8-row x 64-byte transposing reads spread over all banks
+constexpr int kTileK = kPfKTile * kPitchK;
+constexpr int kTileV = kPfKTile * kPitchV;
 
 template <typename T>
-__global__ __launch_bounds__(256) void prefill_chunk_kernel(
+__device__ __forceinline__ f32x16 mfma32(u32x4 a, u32x4 b, f32x16 c);
+template <>
+__device__ __forceinline__ f32x16 mfma32<F16>(u32x4 a, u32x4 b, f32x16 c) {
+  return __builtin_amdgcn_mfma_f32_32x32x16_f16(__builtin_bit_cast(f16x8, a), __builtin_bit_cast(f16x8, b), c, 0, 0, 0);
+}
+template <>
+__device__ __forceinline__ f32x16 mfma32<BF16>(u32x4 a, u32x4 b, f32x16 c) {
+  return __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, a), __builtin_bit_cast(bf16x8, b), c, 0, 0, 0);
+}
+
+// 8-byte transposing LDS read: inside each group of 16 lanes, lane j receives element j%4 of the
+// 8-byte chunks addressed by lanes j/4, 4 + j/4, 8 + j/4 and 12 + j/4 (verified on gfx950).
+__device__ __forceinline__ u32x2 lds_read_tr16(const uint16_t* p) {
+  typedef __attribute__((address_space(3))) s16x4 lds_s16x4;
+  const s16x4 v = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4*)p);
+  return __builtin_bit_cast(u32x2, v);
+}
+
+template <typename T, int HW, bool kPosScale>
+__global__ __launch_bounds__(kPfThreads, 2) void prefill_chunk_kernel(
     const uint16_t* __restrict__ q, const int32_t* __restrict__ cu_q_lens, const uint16_t* __restrict__ k_cache,
     const uint16_t* __restrict__ v_cache, const int32_t* __restrict__ block_table,
     const int32_t* __restrict__ seq_lens, uint16_t* __restrict__ out, int32_t num_q_heads, int32_t num_kv_heads,
     int32_t max_blocks_per_seq, float scale2) {
-  __shared__ __attribute__((aligned(16))) uint16_t k_lds[kKTile * kPitch];
-  __shared__ __attribute__((aligned(16))) uint16_t v_lds[kKTile * kPitch];
+  constexpr int TT = 4 / HW;                       // 32-token tiles per workgroup
+  constexpr int kTokensPerWg = kPfRows * TT;
+  __shared__ __attribute__((aligned(16))) uint16_t k_lds[2][kTileK];
+  __shared__ __attribute__((aligned(16))) uint16_t v_lds[2][kTileV];
 
-  const int qt = blockIdx.x;
-  const int h = blockIdx.y;
-  const int r = blockIdx.z;
+  // Workgroups are dispatched round-robin over the 8 XCDs (each with its own L2) in linear
+  // block order.  All query tiles that read the same K/V -- one (sequence, kv head) -- are
+  // placed on one XCD, so that K/V comes out of that XCD's L2 after the first tile's read.
+  const int n_qt = gridDim.x;                                      // query tiles per (sequence, head slot)
+  const int n_units = gridDim.y * gridDim.z;                       // (head slot, sequence) pairs
+  const int linear = blockIdx.x + n_qt * (blockIdx.y + gridDim.y * blockIdx.z);
+  int qt, unit;
+  if (n_units % kXcds == 0) {
+    const int per_xcd = n_units / kXcds;
+    const int j = linear / kXcds;
+    unit = (j % per_xcd) * kXcds + linear % kXcds;
+    qt = j / per_xcd;
+  } else {                                                         // odd shapes: plain order
+    qt = blockIdx.x;
+    unit = blockIdx.y + gridDim.y * blockIdx.z;
+  }
+  qt = n_qt - 1 - qt;                                              // later tiles see more keys: start them first
+  const int slot = unit % gridDim.y;
+  const int r = unit / gridDim.y;
   const int q_begin = cu_q_lens[r];
   const int lq = cu_q_lens[r + 1] - q_begin;
-  if (qt * kQTile >= lq) return;                                   // uniform over the workgroup
-  const int s_len = min(seq_lens[r], max_blocks_per_seq * kBlockSize);
+  if (qt * kTokensPerWg >= lq) return;                             // uniform over the workgroup
+  const int group = num_q_heads / num_kv_heads;
+  const int subs = group / HW;                                     // workgroups per kv head
+  const int kvh = slot / subs;
+  const int sub = slot % subs;
+  const int s_len = min(max(seq_lens[r], 0), max_blocks_per_seq * kBlockSize);
   const int p0 = max(s_len - lq, 0);                               // absolute position of chunk token 0
-  const int kvh = h / (num_q_heads / num_kv_heads);
   const int32_t* __restrict__ table = block_table + (size_t)r * max_blocks_per_seq;
 
   const int tid = threadIdx.x;
   const int wave = tid >> 6;
   const int lane = tid & 63;
-  const int col = lane & 15;       // query row within the wave's 16 (MFMA column index)
-  const int kg = lane >> 4;        // lane group: contraction slots 8*kg .. 8*kg+7
-
-  const int i_row = qt * kQTile + wave * 16 + col;                 // chunk token of this lane's column
-  const int i_load = min(i_row, lq - 1);
-  const int pq = p0 + i_row;                                       // its absolute position
+  const int col = lane & 31;       // query row within the wave (MFMA column index)
+  const int hg = lane >> 5;        // lane half: contraction slots 8*hg .. 8*hg+7
+  const int h = kvh * group + sub * HW + wave % HW;                // this wave's query head
+  const int tok0 = qt * kTokensPerWg + (wave / HW) * kPfRows;      // its first chunk token
+  const bool wave_has_rows = tok0 < lq;
+  const int i_row = tok0 + col;
+  const int pq = p0 + i_row;                                       // absolute position of this lane's query row
   // keys the workgroup / the wave can see
-  const int wg_kv_end = min(s_len, p0 + min(lq, qt * kQTile + kQTile));
-  const int wave_kv_end = min(s_len, p0 + min(lq, qt * kQTile + wave * 16 + 16));
+  const int wg_kv_end = min(s_len, p0 + min(lq, qt * kTokensPerWg + kTokensPerWg));
+  const int wave_kv_end = wave_has_rows ? min(s_len, p0 + min(lq, tok0 + kPfRows)) : 0;
 
-  u32x4 qf[4];
+  u32x4 qf[8];
   {
-    const uint16_t* src = q + ((size_t)(q_begin + i_load) * num_q_heads + h) * kHeadDim + kg * 8;
+    const uint16_t* src = q + ((size_t)(q_begin + min(i_row, lq - 1)) * num_q_heads + h) * kHeadDim + hg * 8;
 #pragma unroll
-    for (int ks = 0; ks < 4; ++ks) qf[ks] = *reinterpret_cast<const u32x4*>(src + ks * 32);
+    for (int ks = 0; ks < 8; ++ks) qf[ks] = *reinterpret_cast<const u32x4*>(src + ks * 16);
   }
 
-  f32x4 oacc[8];
+  f32x16 oacc[4];
 #pragma unroll
-  for (int db = 0; db < 8; ++db) oacc[db] = f32x4{0.f, 0.f, 0.f, 0.f};
-  float m_run = -INFINITY;
-  float l_run = 0.f;               // partial: this lane group's keys only
+  for (int db = 0; db < 4; ++db)
+#pragma unroll
+    for (int v = 0; v < 16; ++v) oacc[db][v] = 0.f;
+  float m_run = -INFINITY;         // running maximum of the scaled logits (log2 domain)
+  float l_run = 0.f;               // running sum; this lane half's keys only
 
-  const int n_tiles = (wg_kv_end + kKTile - 1) / kKTile;
-  for (int kt = 0; kt < n_tiles; ++kt) {
-    const int k0 = kt * kKTile;
-    __syncthreads();                                               // previous tile fully consumed
+  // Staging registers of the next tile: 4 x 16 bytes of K and of V per thread.  Piece i of a
+  // thread lies in KV block (k0/16 + i) for every thread, so the 4 block ids of a tile are
+  // wave-uniform; they are looked up one tile ahead of the loads that need them.
+  // Loads are unconditional (no branch around them keeps the hardware load counter exact, so
+  // waiting for one register set never drains the other): a key the workgroup cannot see is
+  // replaced by the last key it can see, whose rows are real, finite and already in cache; its
+  // weight is zero through the causal mask.
+  const int kv_last = wg_kv_end - 1;                               // >= 0 here
+  const int last_block = kv_last / kBlockSize;
+  auto lookup = [&](int32_t (&ids)[4], int k0) {
+#pragma unroll
+    for (int i = 0; i < 4; ++i) ids[i] = table[min(k0 / kBlockSize + i, last_block)];
+  };
+  auto fetch = [&](u32x4 (&kst)[4], u32x4 (&vst)[4], const int32_t (&ids)[4], int k0) {
 #pragma unroll
     for (int i = 0; i < 4; ++i) {
-      const int id = tid + 256 * i;                                // 16-byte piece of the 64 x 128 tile
-      const int row = id >> 4;
-      const int c16 = id & 15;
-      const int key = k0 + row;
-      u32x4 kv = u32x4{0u, 0u, 0u, 0u}, vv = u32x4{0u, 0u, 0u, 0u};
-      if (key < s_len) {
-        const size_t off = (((size_t)table[key / kBlockSize] * num_kv_heads + kvh) * kBlockSize + key % kBlockSize) * kHeadDim + c16 * 8;
-        kv = *reinterpret_cast<const u32x4*>(k_cache + off);
-        vv = *reinterpret_cast<const u32x4*>(v_cache + off);
-      }
-      *reinterpret_cast<u32x4*>(&k_lds[row * kPitch + c16 * 8]) = kv;
-      *reinterpret_cast<u32x4*>(&v_lds[row * kPitch + c16 * 8]) = vv;
+      const int id = tid + kPfThreads * i;                         // 16-byte piece of the 64 x 128 tile
+      const int key = min(k0 + (id >> 4), kv_last);                // in block ids[i]
+      const size_t off = (((size_t)ids[i] * num_kv_heads + kvh) * kBlockSize + (key & 15)) * kHeadDim + (id & 15) * 8;
+      kst[i] = *reinterpret_cast<const u32x4*>(k_cache + off);
+      vst[i] = *reinterpret_cast<const u32x4*>(v_cache + off);
     }
-    __syncthreads();
-    if (k0 >= wave_kv_end) continue;                               // whole tile masked for this wave
+  };
+  auto stage = [&](const u32x4 (&kst)[4], const u32x4 (&vst)[4], int buf) {
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      const int id = tid + kPfThreads * i;
+      *reinterpret_cast<u32x4*>(&k_lds[buf][(id >> 4) * kPitchK + (id & 15) * 8]) = kst[i];
+      *reinterpret_cast<u32x4*>(&v_lds[buf][(id >> 4) * kPitchV + (id & 15) * 8]) = vst[i];
+    }
+  };
 
-    // S^T tile: 4 key blocks x (16 keys x 16 query rows)
-    f32x4 sacc[4];
+  // ---- one tile of work for this wave, from LDS buffer `buf`
+  auto compute = [&](int k0, int buf) {
+    if (k0 < wave_kv_end) {
+      const uint16_t* ks_tile = k_lds[buf];
+      const uint16_t* vs_tile = v_lds[buf];
+      // ---- S^T = K . Q^T
+      f32x16 sacc[2];
 #pragma unroll
-    for (int nb = 0; nb < 4; ++nb) {
-      sacc[nb] = f32x4{0.f, 0.f, 0.f, 0.f};
+      for (int sb = 0; sb < 2; ++sb) {
 #pragma unroll
-      for (int ks = 0; ks < 4; ++ks) {
-        const u32x4 kf = *reinterpret_cast<const u32x4*>(&k_lds[(nb * 16 + col) * kPitch + ks * 32 + kg * 8]);
-        sacc[nb] = mfma16<T>(kf, qf[ks], sacc[nb]);
-      }
-    }
-    // scale, causal mask, row maximum
-    float mx = -INFINITY;
+        for (int v = 0; v < 16; ++v) sacc[sb][v] = 0.f;
 #pragma unroll
-    for (int nb = 0; nb < 4; ++nb) {
-#pragma unroll
-      for (int v = 0; v < 4; ++v) {
-        const int key = k0 + nb * 16 + kg * 4 + v;
-        const float s = key <= pq ? sacc[nb][v] * scale2 : -INFINITY;
-        sacc[nb][v] = s;
-        mx = fmaxf(mx, s);
-      }
-    }
-    mx = fmaxf(mx, __shfl_xor(mx, 16));
-    mx = fmaxf(mx, __shfl_xor(mx, 32));
-    const float m_new = fmaxf(m_run, mx);
-    const float m_sub = m_new == -INFINITY ? 0.f : m_new;
-    const float alpha = fast_exp2(m_run - m_sub);
-    m_run = m_new;
-    float psum = 0.f;
-    u32x4 pb[2];
-#pragma unroll
-    for (int t = 0; t < 2; ++t) {
-      float p[8];
-#pragma unroll
-      for (int v = 0; v < 4; ++v) {
-        p[v] = fast_exp2(sacc[2 * t][v] - m_sub);
-        p[4 + v] = fast_exp2(sacc[2 * t + 1][v] - m_sub);
-      }
-#pragma unroll
-      for (int e = 0; e < 8; ++e) psum += p[e];
-#pragma unroll
-      for (int w = 0; w < 4; ++w) pb[t][w] = pack2<T>(p[2 * w], p[2 * w + 1]);
-    }
-    l_run = l_run * alpha + psum;
-#pragma unroll
-    for (int db = 0; db < 8; ++db) oacc[db] *= alpha;
-
-    // O^T += V^T . P^T
-#pragma unroll
-    for (int t = 0; t < 2; ++t) {
-#pragma unroll
-      for (int db = 0; db < 8; ++db) {
-        const uint16_t* vsrc = &v_lds[(t * 32 + kg * 4) * kPitch + db * 16 + col];
-        uint32_t e[8];
-#pragma unroll
-        for (int v = 0; v < 4; ++v) {
-          e[v] = vsrc[v * kPitch];
-          e[4 + v] = vsrc[(16 + v) * kPitch];
+        for (int ks = 0; ks < 8; ++ks) {
+          const u32x4 kf = *reinterpret_cast<const u32x4*>(&ks_tile[(sb * 32 + col) * kPitchK + ks * 16 + hg * 8]);
+          sacc[sb] = mfma32<T>(kf, qf[ks], sacc[sb]);
         }
-        u32x4 vf;
-#pragma unroll
-        for (int w = 0; w < 4; ++w) vf[w] = e[2 * w] | (e[2 * w + 1] << 16);
-        oacc[db] = mfma16<T>(vf, pb[t], oacc[db]);
       }
+      // ---- causal mask (only tiles that reach past the wave's first query position), row maximum
+      const float masked = kPosScale ? -INFINITY : INFINITY;
+      if (k0 + kPfKTile - 1 > p0 + tok0) {
+#pragma unroll
+        for (int sb = 0; sb < 2; ++sb)
+#pragma unroll
+          for (int v = 0; v < 16; ++v) {
+            const int key = k0 + sb * 32 + 8 * (v >> 2) + 4 * hg + (v & 3);
+            if (key > pq) sacc[sb][v] = masked;
+          }
+      }
+      float mx = -INFINITY;          // max over keys of sign(scale) * raw logit
+#pragma unroll
+      for (int sb = 0; sb < 2; ++sb)
+#pragma unroll
+        for (int v = 0; v < 16; ++v) mx = fmaxf(mx, kPosScale ? sacc[sb][v] : -sacc[sb][v]);
+      mx = fmaxf(mx, __shfl_xor(mx, 32));
+      const float m_tile = mx * (kPosScale ? scale2 : -scale2);     // = max of the scaled logits, or -inf
+      const float m_new = fmaxf(m_run, m_tile);
+      const float m_sub = m_new == -INFINITY ? 0.f : m_new;
+      const float alpha = fast_exp2(m_run - m_sub);
+      m_run = m_new;
+      // ---- P^T = exp2(scaled logit - m), packed to the storage type as the B operands
+      float psum = 0.f;
+      u32x4 pb[2][2];
+#pragma unroll
+      for (int sb = 0; sb < 2; ++sb)
+#pragma unroll
+        for (int t = 0; t < 2; ++t)
+#pragma unroll
+          for (int w = 0; w < 4; ++w) {
+            const float pa = fast_exp2(fmaf(sacc[sb][8 * t + 2 * w], scale2, -m_sub));
+            const float pc = fast_exp2(fmaf(sacc[sb][8 * t + 2 * w + 1], scale2, -m_sub));
+            psum += pa + pc;
+            pb[sb][t][w] = pack2<T>(pa, pc);
+          }
+      l_run = l_run * alpha + psum;
+      if (__builtin_amdgcn_ballot_w64(alpha != 1.f) != 0ull) {      // skip the rescale when no row's maximum moved
+#pragma unroll
+        for (int db = 0; db < 4; ++db)
+#pragma unroll
+          for (int v = 0; v < 16; ++v) oacc[db][v] *= alpha;
+      }
+      // ---- O^T += V^T . P^T
+      const int tr_row = (lane & 15) >> 2;                          // which of the 4 keys this lane addresses
+      const int tr_col = 16 * ((lane >> 4) & 1) + 4 * (lane & 3);  // and which 4-dim group
+#pragma unroll
+      for (int sb = 0; sb < 2; ++sb)
+#pragma unroll
+        for (int t = 0; t < 2; ++t) {
+          const uint16_t* vrow = vs_tile + (sb * 32 + 16 * t + 4 * hg + tr_row) * kPitchV + tr_col;
+#pragma unroll
+          for (int db = 0; db < 4; ++db) {
+            const u32x2 lo = lds_read_tr16(vrow + db * 32);                    // keys 16t+4hg+0..3
+            const u32x2 hi = lds_read_tr16(vrow + 8 * kPitchV + db * 32);      // keys 16t+8+4hg+0..3
+            oacc[db] = mfma32<T>(u32x4{lo[0], lo[1], hi[0], hi[1]}, pb[sb][t], oacc[db]);
+          }
+        }
     }
+
+  };
+
+  // Software pipeline over key tiles: while tile kt is used from LDS, tile kt+1 sits in one
+  // register set (loads issued a whole tile earlier) and the loads of tile kt+2 are issued
+  // into the other, so a load has two tile-times to arrive.  Block ids run one tile ahead of
+  // the loads that use them.
+  const int n_tiles = (wg_kv_end + kPfKTile - 1) / kPfKTile;
+  u32x4 ka[4], va[4], kb[4], vb[4];
+  int32_t ids[4];
+  lookup(ids, 0);
+  fetch(ka, va, ids, 0);
+  lookup(ids, kPfKTile);
+  stage(ka, va, 0);
+  __syncthreads();
+  fetch(ka, va, ids, kPfKTile);
+  lookup(ids, 2 * kPfKTile);
+  for (int kt = 0; kt < n_tiles; kt += 2) {
+    // even tile: in LDS buffer 0; tile kt+1 in flight in set a
+    fetch(kb, vb, ids, (kt + 2) * kPfKTile);
+    lookup(ids, (kt + 3) * kPfKTile);
+    compute(kt * kPfKTile, 0);
+    if (kt + 1 >= n_tiles) break;
+    stage(ka, va, 1);
+    __syncthreads();               // tile kt fully consumed by all waves, tile kt+1 visible
+    // odd tile: in LDS buffer 1; tile kt+2 in flight in set b
+    fetch(ka, va, ids, (kt + 3) * kPfKTile);
+    lookup(ids, (kt + 4) * kPfKTile);
+    compute((kt + 1) * kPfKTile, 1);
+    if (kt + 2 >= n_tiles) break;
+    stage(kb, vb, 0);
+    __syncthreads();
   }
 
-  l_run += __shfl_xor(l_run, 16);
   l_run += __shfl_xor(l_run, 32);
-  if (i_row < lq) {
+  if (wave_has_rows && i_row < lq) {
     const float inv = l_run > 0.f ? 1.f / l_run : 0.f;
-    uint16_t* dst = out + ((size_t)(q_begin + i_row) * num_q_heads + h) * kHeadDim + kg * 4;
+    uint16_t* dst = out + ((size_t)(q_begin + i_row) * num_q_heads + h) * kHeadDim + 4 * hg;
 #pragma unroll
-    for (int db = 0; db < 8; ++db) {
-      uint2 o;
-      o.x = pack2<T>(oacc[db][0] * inv, oacc[db][1] * inv);
-      o.y = pack2<T>(oacc[db][2] * inv, oacc[db][3] * inv);
-      *reinterpret_cast<uint2*>(dst + db * 16) = o;
-    }
+    for (int db = 0; db < 4; ++db)
+#pragma unroll
+      for (int j = 0; j < 4; ++j) {                                 // dims db*32 + 8j + 4hg + 0..3
+        u32x2 o;
+        o[0] = pack2<T>(oacc[db][4 * j] * inv, oacc[db][4 * j + 1] * inv);
+        o[1] = pack2<T>(oacc[db][4 * j + 2] * inv, oacc[db][4 * j + 3] * inv);
+        *reinterpret_cast<u32x2*>(dst + db * 32 + 8 * j) = o;
+      }
+  }
+}
+
+template <typename T, int HW>
+static int launch_hw(const vtc_attn_params& p, int32_t num_seqs, const void* q, const int32_t* cu_q_lens,
+                     int32_t max_q_len, const void* k_cache, const void* v_cache, const int32_t* block_table,
+                     const int32_t* seq_lens, void* out, hipStream_t stream) {
+  constexpr int kTokensPerWg = kPfRows * (4 / HW);
+  const int group = p.num_q_heads / p.num_kv_heads;
+  const long long gy = (long long)p.num_kv_heads * (group / HW);
+  if (num_seqs > 65535 || gy > 65535) return VTC_ERR_UNSUPPORTED;
+  dim3 grid((max_q_len + kTokensPerWg - 1) / kTokensPerWg, (unsigned)gy, num_seqs);
+  float scale2 = p.scale * kLog2e;
+  if (scale2 == 0.f) scale2 = 1e-30f;   // all logits equal either way; keeps (-inf) * scale of masked keys well defined
+  auto go = [&](auto kernel) {
+    hipLaunchKernelGGL(kernel, grid, dim3(kPfThreads), 0, stream, static_cast<const uint16_t*>(q), cu_q_lens,
+                       static_cast<const uint16_t*>(k_cache), static_cast<const uint16_t*>(v_cache), block_table,
+                       seq_lens, static_cast<uint16_t*>(out), p.num_q_heads, p.num_kv_heads, p.max_blocks_per_seq,
+                       scale2);
+  };
+  if (scale2 >= 0.f)
+    go(prefill_chunk_kernel<T, HW, true>);
+  else
+    go(prefill_chunk_kernel<T, HW, false>);
+  return hipGetLastError() == hipSuccess ? VTC_OK : VTC_ERR_HIP;
+}
+
+template <typename T>
+static int launch_t(const vtc_attn_params& p, int32_t num_seqs, const void* q, const int32_t* cu_q_lens,
+                    int32_t max_q_len, const void* k_cache, const void* v_cache, const int32_t* block_table,
+                    const int32_t* seq_lens, void* out, hipStream_t stream) {
+  switch (p.num_q_heads / p.num_kv_heads) {
+    case 1: return launch_hw<T, 1>(p, num_seqs, q, cu_q_lens, max_q_len, k_cache, v_cache, block_table, seq_lens, out, stream);
+    case 2: return launch_hw<T, 2>(p, num_seqs, q, cu_q_lens, max_q_len, k_cache, v_cache, block_table, seq_lens, out, stream);
+    default: return launch_hw<T, 4>(p, num_seqs, q, cu_q_lens, max_q_len, k_cache, v_cache, block_table, seq_lens, out, stream);
   }
 }
 
 int launch_prefill(const vtc_attn_params& p, int32_t num_seqs, const void* q, const int32_t* cu_q_lens,
                    int32_t max_q_len, const void* k_cache, const void* v_cache, const int32_t* block_table,
                    const int32_t* seq_lens, void* out, hipStream_t stream) {
-  if (num_seqs > 65535 || p.num_q_heads > 65535) return VTC_ERR_UNSUPPORTED;
-  dim3 grid((max_q_len + kQTile - 1) / kQTile, p.num_q_heads, num_seqs);
-  const float scale2 = p.scale * kLog2e;
   if (p.dtype == VTC_F16)
-    hipLaunchKernelGGL(prefill_chunk_kernel<F16>, grid, dim3(256), 0, stream, static_cast<const uint16_t*>(q),
-                       cu_q_lens, static_cast<const uint16_t*>(k_cache), static_cast<const uint16_t*>(v_cache),
-                       block_table, seq_lens, static_cast<uint16_t*>(out), p.num_q_heads, p.num_kv_heads,
-                       p.max_blocks_per_seq, scale2);
-  else
-    hipLaunchKernelGGL(prefill_chunk_kernel<BF16>, grid, dim3(256), 0, stream, static_cast<const uint16_t*>(q),
-                       cu_q_lens, static_cast<const uint16_t*>(k_cache), static_cast<const uint16_t*>(v_cache),
-                       block_table, seq_lens, static_cast<uint16_t*>(out), p.num_q_heads, p.num_kv_heads,
-                       p.max_blocks_per_seq, scale2);
-  return hipGetLastError() == hipSuccess ? VTC_OK : VTC_ERR_HIP;
+    return launch_t<F16>(p, num_seqs, q, cu_q_lens, max_q_len, k_cache, v_cache, block_table, seq_lens, out, stream);
+  return launch_t<BF16>(p, num_seqs, q, cu_q_lens, max_q_len, k_cache, v_cache, block_table, seq_lens, out, stream);
 }
 
 }  // namespace vtc

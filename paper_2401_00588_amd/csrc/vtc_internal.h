@@ -95,14 +95,11 @@ __device__ __forceinline__ uint32_t pack2<F16>(float a, float b) {
   f16x2 v = {(_Float16)a, (_Float16)b};
   return __builtin_bit_cast(uint32_t, v);
 }
-__device__ __forceinline__ uint32_t bf16_bits(float x) {
-  uint32_t u = __builtin_bit_cast(uint32_t, x);
-  if ((u & 0x7fffffffu) > 0x7f800000u) return (u >> 16) | 0x40u;   // keep NaN a NaN
-  return (u + 0x7fffu + ((u >> 16) & 1u)) >> 16;
-}
 template <>
 __device__ __forceinline__ uint32_t pack2<BF16>(float a, float b) {
-  return bf16_bits(a) | (bf16_bits(b) << 16);
+  using f32x2 = float __attribute__((ext_vector_type(2)));
+  const f32x2 v = {a, b};
+  return __builtin_bit_cast(uint32_t, __builtin_convertvector(v, bf16x2));   // v_cvt_pk_bf16_f32, nearest even
 }
 
 // ---- cross-lane helpers -----------------------------------------------------
