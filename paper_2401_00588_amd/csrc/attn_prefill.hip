@@ -38,6 +38,7 @@ constexpr int kPfKTile = 64;             // keys per LDS tile
 constexpr int kPitchK = kHeadDim + 8;    // 272 B rows: 16-byte reads of 16 consecutive rows hit all banks once
 constexpr int kPitchV = kHeadDim + 32;   // 320 B rows: the 8-row x 64-byte transposing reads spread over all banks
 constexpr int kTileK = kPfKTile * kPitchK;
+static_assert(4 * kPfRows * kPitchK <= 2 * kPfKTile * kPitchK, "the four output patches must fit the K buffers");
 constexpr int kTileV = kPfKTile * kPitchV;
 
 template <typename T>
@@ -271,19 +272,31 @@ __global__ __launch_bounds__(kPfThreads, 2) void prefill_chunk_kernel(
     __syncthreads();
   }
 
+  // ---- epilogue: normalise, round, and turn the wave's O^T (a query row per lane) into whole
+  // 256-byte output rows through a private 32 x 128 LDS patch, so that the global stores are
+  // 16 bytes per lane and contiguous per row.
   l_run += __shfl_xor(l_run, 32);
-  if (wave_has_rows && i_row < lq) {
+  __syncthreads();                                                 // every wave is done reading the K tiles
+  if (wave_has_rows) {
+    uint16_t* patch = &k_lds[0][0] + wave * (kPfRows * kPitchK);   // 4 patches fill the two K buffers exactly
     const float inv = l_run > 0.f ? 1.f / l_run : 0.f;
-    uint16_t* dst = out + ((size_t)(q_begin + i_row) * num_q_heads + h) * kHeadDim + 4 * hg;
 #pragma unroll
     for (int db = 0; db < 4; ++db)
 #pragma unroll
-      for (int j = 0; j < 4; ++j) {                                 // dims db*32 + 8j + 4hg + 0..3
+      for (int j = 0; j < 4; ++j) {                                 // dims db*32 + 8j + 4hg + 0..3 of row `col`
         u32x2 o;
         o[0] = pack2<T>(oacc[db][4 * j] * inv, oacc[db][4 * j + 1] * inv);
         o[1] = pack2<T>(oacc[db][4 * j + 2] * inv, oacc[db][4 * j + 3] * inv);
-        *reinterpret_cast<u32x2*>(dst + db * 32 + 8 * j) = o;
+        *reinterpret_cast<u32x2*>(&patch[col * kPitchK + db * 32 + 8 * j + 4 * hg]) = o;
       }
+    // LDS operations of one wave complete in order: the reads below see the writes above
+#pragma unroll
+    for (int i = 0; i < 8; ++i) {
+      const int row = 4 * i + (lane >> 4);
+      const u32x4 v = *reinterpret_cast<const u32x4*>(&patch[row * kPitchK + (lane & 15) * 8]);
+      if (tok0 + row < lq)
+        *reinterpret_cast<u32x4*>(out + ((size_t)(q_begin + tok0 + row) * num_q_heads + h) * kHeadDim + (lane & 15) * 8) = v;
+    }
   }
 }
 
