@@ -29,6 +29,22 @@ HBM_PEAK_GBS = 8000.0          # MI355X HBM3E, published
 MFMA_PEAK_TFLOPS = 2500.0      # dense bf16 / fp16
 EVENT_EVERY = 5                # steps between two kernel-level HIP event pairs
 
+# HBM bytes per launch of decode_attend_kernel on cfg3 from rocprofv3 FETCH_SIZE / WRITE_SIZE counters, scaled
+# by the copy-kernel calibration (profiles/decode_attend_cfg3_hbm_bytes.md).  Valid only for the kernel
+# source the counters were taken with: keyed by the SHA-256 of the two files that define that kernel.
+DECODE_TRAFFIC_CFG3 = {
+}
+
+
+def decode_kernel_fingerprint() -> str:
+    import hashlib
+
+    h = hashlib.sha256()
+    for name in ("attn_decode.hip", "vtc_internal.h"):
+        with open(os.path.join(ROOT, "paper_2401_00588_amd", "csrc", name), "rb") as fh:
+            h.update(fh.read())
+    return h.hexdigest()[:16]
+
 
 def parse_args():
     ap = argparse.ArgumentParser()
@@ -215,7 +231,7 @@ def main() -> int:
             "peak": HBM_PEAK_GBS,
             "unit": "GB/s",
             "frac": round(achieved / HBM_PEAK_GBS, 4),
-            "traffic": None,
+            "traffic": DECODE_TRAFFIC_CFG3.get(decode_kernel_fingerprint()) if cfg == 3 else None,
             "kernel_avg_ms": round(kernel_avg_ms, 5),
             "kernel_min_ms": round(kernel_ms[0], 5),
             "kernel_median_ms": round(kernel_ms[len(kernel_ms) // 2], 5),

@@ -138,3 +138,28 @@ def paged_prefill_chunk(
         row = int(cu_q_lens[r]) + i
         out[row, h] = attend_one(widen(q_bits[row, h], dtype), keys[: p + 1], values[: p + 1], scale)
     return out
+
+
+def kv_append(
+    k_cache: np.ndarray,         # [num_blocks, Hkv, Bs, D] uint16, modified in place
+    v_cache: np.ndarray,
+    k_new: np.ndarray,           # [T, Hkv, D] uint16, new tokens of all sequences concatenated
+    v_new: np.ndarray,
+    cu_new_lens: Sequence[int],  # [N+1] prefix sums of the number of new tokens per sequence
+    block_table: np.ndarray,
+    seq_lens: Sequence[int],     # [N] context length AFTER the append
+) -> None:
+    """Write the K/V rows of newly processed tokens into the paged cache (the step that precedes attention).
+
+    New token i of sequence r (of n_r = cu[r+1]-cu[r] new ones) gets absolute position p = seq_len_r - n_r + i
+    and lands in block block_table[r][p // Bs], row p % Bs, for every KV head.  Pure data movement.
+    """
+    bs = k_cache.shape[2]
+    for r in range(len(cu_new_lens) - 1):
+        n_r = int(cu_new_lens[r + 1]) - int(cu_new_lens[r])
+        for i in range(n_r):
+            p = int(seq_lens[r]) - n_r + i
+            blk = int(block_table[r][p // bs])
+            t = int(cu_new_lens[r]) + i
+            k_cache[blk, :, p % bs, :] = k_new[t]
+            v_cache[blk, :, p % bs, :] = v_new[t]

@@ -36,6 +36,16 @@ Points the paper leaves open, and the reading taken here:
 
 ``lift=False`` gives the Least Counter First baseline of Section 5.1.
 
+Two variants of the paper are switched on by constructor arguments:
+  * ``cost=h`` (Section 4.2 / Algorithm 4): admission charges h(n_p, 0) and a decode step charges
+    h(n_p, n_q) - h(n_p, n_q - 1) per running request; ``h`` is any callable on integers.  With
+    h = w_p*n_p + w_q*n_q this is Algorithm 2 again.
+  * ``predictor`` (Section 4.4 / Algorithm 3): admission also charges w_q * predicted_output_len(r);
+    after a decode step a request is charged w_q only once its output exceeds the prediction, and
+    when it finishes short of the prediction the unused part w_q * (output - predicted) is refunded.
+    ``predictor(client, request)`` returns the predicted length; ``LastFivePredictor`` is the paper's
+    "average output length of the last five requests of the client" (integer floor, 0 without history).
+
 TEST INFRASTRUCTURE ONLY.
 """
 from __future__ import annotations
@@ -52,6 +62,21 @@ class Running:
     n_input: int
     n_output: int      # hidden: only compared with ``generated`` to detect the end
     generated: int = 0
+    predicted: int = 0  # predicted output length (Algorithm 3); unused otherwise
+
+
+class LastFivePredictor:
+    """Mean output length of the client's last five finished requests (Section 5.1, "VTC (predict)")."""
+
+    def __init__(self, num_clients: int) -> None:
+        self.history = [deque(maxlen=5) for _ in range(num_clients)]
+
+    def __call__(self, client: int, request) -> int:
+        h = self.history[client]
+        return sum(h) // len(h) if h else 0
+
+    def observe(self, client: int, n_output: int) -> None:
+        self.history[client].append(int(n_output))
 
 
 @dataclass
@@ -82,6 +107,8 @@ class VTCScheduler:
         max_batch: Optional[int] = None,
         lift: bool = True,
         observer: Optional[Observer] = None,
+        cost: Optional[Callable[[int, int], int]] = None,
+        predictor: Optional[Callable] = None,
     ) -> None:
         self.num_clients = num_clients
         self.w_p, self.w_q = int(w_p), int(w_q)
@@ -89,6 +116,10 @@ class VTCScheduler:
         self.max_batch = max_batch
         self.lift = lift
         self.observer = observer
+        self.cost = cost
+        self.predictor = predictor
+        if cost is not None and predictor is not None:
+            raise ValueError("the paper defines length prediction for the weighted-token cost only")
         self.c: List[int] = [0] * num_clients                      # virtual token counters
         self.Q: List[Deque] = [deque() for _ in range(num_clients)]  # waiting queue, per client
         self.B: List[Running] = []                                  # running batch
@@ -136,9 +167,17 @@ class VTCScheduler:
             r = self.Q[k][0]                                # earliest request of k
             if not self._fits(r, B_new, new_reserved):
                 break
-            self.c[k] += self.w_p * r.n_input
-            self.service[k] += self.w_p * r.n_input
-            B_new.append(Running(r.rid, r.client, r.n_input, r.n_output))
+            run = Running(r.rid, r.client, r.n_input, r.n_output)
+            if self.cost is not None:
+                self.c[k] += self.cost(r.n_input, 0)
+                self.service[k] += self.cost(r.n_input, 0)
+            else:
+                self.c[k] += self.w_p * r.n_input
+                self.service[k] += self.w_p * r.n_input
+                if self.predictor is not None:
+                    run.predicted = int(self.predictor(k, r))
+                    self.c[k] += self.w_q * run.predicted       # pre-payment; not service received yet
+            B_new.append(run)
             new_reserved += r.n_input + self.L_output
             self.Q[k].popleft()
             if not self.Q[k]:
@@ -169,10 +208,24 @@ class VTCScheduler:
         )
         for x in self.B:
             x.generated += 1
-        for i in range(self.num_clients):
-            n_i = sum(1 for x in self.B if x.client == i)
-            self.c[i] += self.w_q * n_i
-            self.service[i] += self.w_q * n_i
+        if self.cost is not None:
+            for x in self.B:
+                d = self.cost(x.n_input, x.generated) - self.cost(x.n_input, x.generated - 1)
+                self.c[x.client] += d
+                self.service[x.client] += d
+        elif self.predictor is not None:
+            for x in self.B:
+                self.service[x.client] += self.w_q
+                delta = x.generated - x.predicted
+                if delta > 0:
+                    self.c[x.client] += self.w_q
+                if x.generated >= x.n_output and delta < 0:
+                    self.c[x.client] += self.w_q * delta
+        else:
+            for i in range(self.num_clients):
+                n_i = sum(1 for x in self.B if x.client == i)
+                self.c[i] += self.w_q * n_i
+                self.service[i] += self.w_q * n_i
         rec.counters_after_decode_charge = list(self.c)
         self._notify("decode")
         # filter_finished_requests(B)
@@ -180,6 +233,8 @@ class VTCScheduler:
         self.B = [x for x in self.B if x.generated < x.n_output]
         for x in rec.finished:
             self.reserved -= x.n_input + self.L_output
+            if self.predictor is not None and hasattr(self.predictor, "observe"):
+                self.predictor.observe(x.client, x.generated)
         self.iteration += 1
         return rec
 

@@ -283,3 +283,30 @@ def test_row_subset_computes_only_the_requested_rows():
     part = A.paged_decode(q, kc, vc, table, sl, 0.3, "f16", rows=[(2, 3), (0, 1)])
     assert np.array_equal(part[2, 3], full[2, 3]) and np.array_equal(part[0, 1], full[0, 1])
     assert np.isnan(part[1]).all()
+
+
+# ------------------------------------------------------------------ KV append
+def test_kv_append_puts_rows_where_attention_reads_them():
+    rng = np.random.default_rng(16)
+    dtype, hkv, d, bs = "f16", 2, 8, 4
+    seq_after = [5, 9, 1, 16]
+    n_new = [1, 4, 1, 0]
+    keys = [rng.standard_normal((s, hkv, d), dtype=np.float32) for s in seq_after]
+    vals = [rng.standard_normal((s, hkv, d), dtype=np.float32) for s in seq_after]
+    # cache filled with the old tokens only; the slots of the new tokens hold NaN
+    kc, vc, table, _ = pack_paged(keys, vals, bs, dtype, rng)
+    full_k, full_v = kc.copy(), vc.copy()
+    for r, (s, n) in enumerate(zip(seq_after, n_new)):
+        for p in range(s - n, s):
+            kc[table[r, p // bs], :, p % bs, :] = NAN_BITS[dtype]
+            vc[table[r, p // bs], :, p % bs, :] = NAN_BITS[dtype]
+    cu = np.concatenate([[0], np.cumsum(n_new)])
+    k_new = np.concatenate([f32_to_storage_bits(keys[r][s - n:s], dtype) for r, (s, n) in enumerate(zip(seq_after, n_new))])
+    v_new = np.concatenate([f32_to_storage_bits(vals[r][s - n:s], dtype) for r, (s, n) in enumerate(zip(seq_after, n_new))])
+    A.kv_append(kc, vc, k_new, v_new, cu, table, seq_after)
+    assert np.array_equal(kc, full_k) and np.array_equal(vc, full_v)       # exactly the new slots were written
+    for r, s in enumerate(seq_after):
+        for g in range(hkv):
+            got = A.gather_sequence(kc, table[r], s, g, dtype)
+            want = bits_to_f64_via_torch(f32_to_storage_bits(keys[r][:, g], dtype), dtype)
+            assert np.array_equal(got, want)
