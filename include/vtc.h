@@ -170,6 +170,86 @@ int vtc_counter_update(int64_t* counters, int32_t num_clients, const int32_t* cl
                        int64_t w_p, int64_t w_q, void* hip_stream);
 
 /*
+ * Integer (fixed-point) cost polynomial
+ *     h(n_p, n_q) = c0 + cp*n_p + cq*n_q + cpp*n_p^2 + cpq*n_p*n_q + cqq*n_q^2
+ * for the general cost function of Section 4.2.  The weighted-token cost of Section 3.1 is
+ * {0, w_p, w_q, 0, 0, 0}; the profiled cost printed in Appendix B.2,
+ * 2.1 n_p + n_q + 0.04 n_p n_q + 0.032 n_q^2 + 11.46, is {11460, 2100, 1000, 0, 40, 32} in units of 1/1000.
+ */
+typedef struct {
+  int64_t c0, cp, cq, cpp, cpq, cqq;
+} vtc_cost_poly;
+
+/*
+ * General VTC counter update (Algorithm 4: "when new tokens have been processed",
+ * c_i += sum over the client's requests of h(n_p, n_q) - h(n_p(old), n_q(old)); Section 4.2
+ * gives the two instances used by Algorithm 2: h(n_p, 0) at admission and
+ * h(n_p, n_q) - h(n_p, n_q - 1) per decode step):
+ *     counters[client_ids[r]] += (h(n_p_new[r], n_q_new[r]) - old_r) * mult
+ * with old_r = 0 if n_p_old[r] == n_q_old[r] == 0 (none of the request's tokens processed yet, so the
+ * first update charges h(n_p, 0) in full, constant term included) and h(n_p_old[r], n_q_old[r])
+ * otherwise; mult = client_multiplier[client_ids[r]], or 1 if client_multiplier is NULL.  The
+ * multiplier expresses weighted VTC (Section 4.3) exactly: dividing client i's increment by its
+ * weight w_i is multiplying it by W / w_i for a common multiple W of the weights.
+ * Exact two's-complement int64 arithmetic, independent of summation order; client ids outside
+ * [0, num_clients) are ignored.
+ *
+ *   counters [device]           int64 [num_clients], updated in place
+ *   client_ids [device]         int32 [n]
+ *   n_p_old, n_q_old,
+ *   n_p_new, n_q_new [device]   int32 [n], processed input / output tokens before and after
+ *   h [host]                    cost polynomial
+ *   client_multiplier [device]  int64 [num_clients] or NULL
+ * n == 0 is a successful no-op.
+ */
+int vtc_counter_update_cost(int64_t* counters, int32_t num_clients, const int32_t* client_ids,
+                            const int32_t* n_p_old, const int32_t* n_q_old, const int32_t* n_p_new,
+                            const int32_t* n_q_new, int32_t n, const vtc_cost_poly* h /*[host]*/,
+                            const int64_t* client_multiplier, void* hip_stream);
+
+/*
+ * Per-step counter adjustment of VTC with length prediction (Algorithm 3, the loop after
+ * forward_decode; Section 4.4).  At admission the caller has charged
+ * w_p * input_len + w_q * predicted_output_len with vtc_counter_update.  After each decode step,
+ * for every running request r, with delta = n_output[r] - n_predicted[r] (n_output counts the token
+ * just generated):
+ *     delta > 0                    : counters[client] += w_q          (prediction used up)
+ *     finished[r] != 0 and delta<0 : counters[client] += w_q * delta  (refund of the unused part)
+ * so that a finished request has paid w_p*n_p + w_q*n_q whatever was predicted.
+ * Exact int64 arithmetic; client ids outside [0, num_clients) are ignored.
+ *
+ *   counters [device]     int64 [num_clients], updated in place
+ *   client_ids, n_output, n_predicted, finished [device]   int32 [n]
+ * n == 0 is a successful no-op.
+ */
+int vtc_counter_update_predicted(int64_t* counters, int32_t num_clients, const int32_t* client_ids,
+                                 const int32_t* n_output, const int32_t* n_predicted,
+                                 const int32_t* finished, int32_t n, int64_t w_q, void* hip_stream);
+
+/*
+ * Append newly processed tokens to the paged cache -- the step that precedes the attention
+ * calls above, which expect the current token / chunk to be cached already (Algorithm 2 runs
+ * forward_prefill and forward_decode on the running batch's KV memory pool).
+ *
+ * Sequence r contributes n_r = cu_new_lens[r+1] - cu_new_lens[r] tokens, stored at rows
+ * cu_new_lens[r] .. of k_new / v_new.  seq_lens[r] is the context length AFTER the append
+ * (the value the attention call will be given): new token i gets position
+ * p = seq_lens[r] - n_r + i and is written to block block_table[r][p / block_size], row
+ * p % block_size, of every KV head.  Bit-exact copy.  The blocks must be allocated by the caller.
+ *
+ *   k_new, v_new [device]   E [total_new_tokens, num_kv_heads, 128]
+ *   cu_new_lens [device]    int32 [num_seqs + 1], cu_new_lens[0] == 0
+ *   max_new_len             host-side upper bound on every n_r (sizes the launch)
+ *   k_cache, v_cache        [device] paged caches, written
+ *   block_table, seq_lens   [device] as for the attention calls
+ * num_seqs == 0 or max_new_len == 0 is a successful no-op.
+ */
+int vtc_kv_append(const vtc_attn_params* params /*[host]*/, int32_t num_seqs, const void* k_new,
+                  const void* v_new, const int32_t* cu_new_lens, int32_t max_new_len, void* k_cache,
+                  void* v_cache, const int32_t* block_table, const int32_t* seq_lens,
+                  void* hip_stream);
+
+/*
  * Test hook for the paged-cache index arithmetic: writes, for every sequence r
  * and position p < seq_lens[r], the physical slot
  *     slot(r,p) = block_table[r][p / block_size] * block_size + p % block_size

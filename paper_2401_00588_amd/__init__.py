@@ -7,6 +7,7 @@ raises.
 """
 from .binding import (  # noqa: F401
     AttnParams,
+    CostPoly,
     HipEvent,
     VTC_BF16,
     VTC_F16,
@@ -18,6 +19,9 @@ from .binding import (  # noqa: F401
     vtc_attn_prefill_chunk,
     vtc_attn_workspace_bytes,
     vtc_counter_update,
+    vtc_counter_update_cost,
+    vtc_counter_update_predicted,
+    vtc_kv_append,
     vtc_debug_gather_slots,
     vtc_strerror,
     vtc_version,

@@ -38,6 +38,12 @@ class AttnParams(ctypes.Structure):
     ]
 
 
+class CostPoly(ctypes.Structure):
+    """Mirror of ``vtc_cost_poly``: h = c0 + cp*n_p + cq*n_q + cpp*n_p^2 + cpq*n_p*n_q + cqq*n_q^2."""
+
+    _fields_ = [(name, ctypes.c_int64) for name in ("c0", "cp", "cq", "cpp", "cpq", "cqq")]
+
+
 def library_path() -> str:
     return os.path.join(_HERE, _LIB_NAME)
 
@@ -70,6 +76,12 @@ def load_library() -> ctypes.CDLL:
     lib.vtc_attn_prefill_chunk.argtypes = [P, i32, vp, vp, i32, vp, vp, vp, vp, vp, vp, sz, vp]
     lib.vtc_counter_update.restype = ctypes.c_int
     lib.vtc_counter_update.argtypes = [vp, i32, vp, vp, vp, i32, i64, i64, vp]
+    lib.vtc_counter_update_cost.restype = ctypes.c_int
+    lib.vtc_counter_update_cost.argtypes = [vp, i32, vp, vp, vp, vp, vp, i32, ctypes.POINTER(CostPoly), vp, vp]
+    lib.vtc_counter_update_predicted.restype = ctypes.c_int
+    lib.vtc_counter_update_predicted.argtypes = [vp, i32, vp, vp, vp, vp, i32, i64, vp]
+    lib.vtc_kv_append.restype = ctypes.c_int
+    lib.vtc_kv_append.argtypes = [P, i32, vp, vp, vp, i32, vp, vp, vp, vp, vp]
     lib.vtc_debug_gather_slots.restype = ctypes.c_int
     lib.vtc_debug_gather_slots.argtypes = [P, i32, vp, vp, vp, i32, vp, vp]
     _lib = lib
@@ -270,6 +282,79 @@ def vtc_counter_update(counters, client_ids, n_input_tokens, n_output_tokens, w_
     if rc != 0:
         raise VtcError(rc, "vtc_counter_update")
     return counters
+
+
+def vtc_counter_update_cost(counters, client_ids, n_p_old, n_q_old, n_p_new, n_q_new, h: CostPoly,
+                            client_multiplier=None):
+    """counters[client] += (h(new) - h(old)) * multiplier[client], in place (general / weighted VTC)."""
+    torch = _torch()
+    lib = load_library()
+    _check(counters, "counters", torch.int64, 1)
+    _check(client_ids, "client_ids", torch.int32, 1)
+    n = int(client_ids.shape[0])
+    for name, t in (("n_p_old", n_p_old), ("n_q_old", n_q_old), ("n_p_new", n_p_new), ("n_q_new", n_q_new)):
+        _check(t, name, torch.int32, 1)
+        if t.shape[0] != n:
+            raise ValueError(f"{name} must have one entry per request")
+    if client_multiplier is not None:
+        _check(client_multiplier, "client_multiplier", torch.int64, 1)
+        if client_multiplier.shape[0] != counters.shape[0]:
+            raise ValueError("client_multiplier must have one entry per client")
+    rc = lib.vtc_counter_update_cost(counters.data_ptr(), int(counters.shape[0]), client_ids.data_ptr(),
+                                     n_p_old.data_ptr(), n_q_old.data_ptr(), n_p_new.data_ptr(), n_q_new.data_ptr(),
+                                     n, ctypes.byref(h),
+                                     None if client_multiplier is None else client_multiplier.data_ptr(), _stream())
+    if rc != 0:
+        raise VtcError(rc, "vtc_counter_update_cost")
+    return counters
+
+
+def vtc_counter_update_predicted(counters, client_ids, n_output, n_predicted, finished, w_q: int):
+    """Per-step adjustment of VTC with length prediction, in place."""
+    torch = _torch()
+    lib = load_library()
+    _check(counters, "counters", torch.int64, 1)
+    _check(client_ids, "client_ids", torch.int32, 1)
+    n = int(client_ids.shape[0])
+    for name, t in (("n_output", n_output), ("n_predicted", n_predicted), ("finished", finished)):
+        _check(t, name, torch.int32, 1)
+        if t.shape[0] != n:
+            raise ValueError(f"{name} must have one entry per request")
+    rc = lib.vtc_counter_update_predicted(counters.data_ptr(), int(counters.shape[0]), client_ids.data_ptr(),
+                                          n_output.data_ptr(), n_predicted.data_ptr(), finished.data_ptr(), n,
+                                          int(w_q), _stream())
+    if rc != 0:
+        raise VtcError(rc, "vtc_counter_update_predicted")
+    return counters
+
+
+def vtc_kv_append(params: AttnParams, k_new, v_new, cu_new_lens, max_new_len: int, k_cache, v_cache, block_table,
+                  seq_lens):
+    """Write the new tokens' K/V rows into the paged cache (in place)."""
+    torch = _torch()
+    lib = load_library()
+    elt = _elt_dtype(params)
+    _check(k_new, "k_new", elt, 3)
+    _check(v_new, "v_new", elt, 3)
+    _check(cu_new_lens, "cu_new_lens", torch.int32, 1)
+    _check(k_cache, "k_cache", elt, 4)
+    _check(v_cache, "v_cache", elt, 4)
+    _check(block_table, "block_table", torch.int32, 2)
+    _check(seq_lens, "seq_lens", torch.int32, 1)
+    n = int(seq_lens.shape[0])
+    if cu_new_lens.shape[0] != n + 1:
+        raise ValueError("cu_new_lens must be [num_seqs + 1]")
+    if tuple(k_new.shape[1:]) != (params.num_kv_heads, params.head_dim) or k_new.shape != v_new.shape:
+        raise ValueError("k_new / v_new must be [total_new_tokens, num_kv_heads, head_dim]")
+    if tuple(k_cache.shape[1:]) != (params.num_kv_heads, params.block_size, params.head_dim) or k_cache.shape != v_cache.shape:
+        raise ValueError("k_cache / v_cache must be [num_blocks, num_kv_heads, block_size, head_dim]")
+    if tuple(block_table.shape) != (n, params.max_blocks_per_seq):
+        raise ValueError("block_table must be [num_seqs, max_blocks_per_seq]")
+    rc = lib.vtc_kv_append(ctypes.byref(params), n, k_new.data_ptr(), v_new.data_ptr(), cu_new_lens.data_ptr(),
+                           int(max_new_len), k_cache.data_ptr(), v_cache.data_ptr(), block_table.data_ptr(),
+                           seq_lens.data_ptr(), _stream())
+    if rc != 0:
+        raise VtcError(rc, "vtc_kv_append")
 
 
 def vtc_debug_gather_slots(params: AttnParams, block_table, seq_lens, cu_out, max_seq_len: int, slots_out):

@@ -24,7 +24,7 @@ int device_cu_count() {
 
 extern "C" {
 
-int vtc_version(void) { return 100; }
+int vtc_version(void) { return 200; }
 
 const char* vtc_strerror(int code) {
   switch (code) {
@@ -98,6 +98,42 @@ int vtc_counter_update(int64_t* counters, int32_t num_clients, const int32_t* cl
   if (!counters || !client_ids) return VTC_ERR_INVALID_ARG;
   return vtc::launch_counter_update(counters, num_clients, client_ids, n_input_tokens, n_output_tokens, n, w_p,
                                     w_q, static_cast<hipStream_t>(hip_stream));
+}
+
+int vtc_counter_update_cost(int64_t* counters, int32_t num_clients, const int32_t* client_ids,
+                            const int32_t* n_p_old, const int32_t* n_q_old, const int32_t* n_p_new,
+                            const int32_t* n_q_new, int32_t n, const vtc_cost_poly* h,
+                            const int64_t* client_multiplier, void* hip_stream) {
+  if (n < 0 || num_clients < 0 || !h) return VTC_ERR_INVALID_ARG;
+  if (n == 0 || num_clients == 0) return VTC_OK;
+  if (!counters || !client_ids || !n_p_old || !n_q_old || !n_p_new || !n_q_new) return VTC_ERR_INVALID_ARG;
+  return vtc::launch_counter_update_cost(counters, num_clients, client_ids, n_p_old, n_q_old, n_p_new, n_q_new, n, *h,
+                                         client_multiplier, static_cast<hipStream_t>(hip_stream));
+}
+
+int vtc_counter_update_predicted(int64_t* counters, int32_t num_clients, const int32_t* client_ids,
+                                 const int32_t* n_output, const int32_t* n_predicted, const int32_t* finished,
+                                 int32_t n, int64_t w_q, void* hip_stream) {
+  if (n < 0 || num_clients < 0) return VTC_ERR_INVALID_ARG;
+  if (n == 0 || num_clients == 0) return VTC_OK;
+  if (!counters || !client_ids || !n_output || !n_predicted || !finished) return VTC_ERR_INVALID_ARG;
+  return vtc::launch_counter_update_predicted(counters, num_clients, client_ids, n_output, n_predicted, finished, n,
+                                              w_q, static_cast<hipStream_t>(hip_stream));
+}
+
+int vtc_kv_append(const vtc_attn_params* params, int32_t num_seqs, const void* k_new, const void* v_new,
+                  const int32_t* cu_new_lens, int32_t max_new_len, void* k_cache, void* v_cache,
+                  const int32_t* block_table, const int32_t* seq_lens, void* hip_stream) {
+  int rc = vtc::check_params(params);
+  if (rc != VTC_OK) return rc;
+  if (num_seqs < 0 || max_new_len < 0) return VTC_ERR_INVALID_ARG;
+  if (num_seqs == 0 || max_new_len == 0) return VTC_OK;
+  if (!k_new || !v_new || !cu_new_lens || !k_cache || !v_cache || !block_table || !seq_lens) return VTC_ERR_INVALID_ARG;
+  if ((reinterpret_cast<uintptr_t>(k_new) & 15u) || (reinterpret_cast<uintptr_t>(v_new) & 15u) ||
+      (reinterpret_cast<uintptr_t>(k_cache) & 15u) || (reinterpret_cast<uintptr_t>(v_cache) & 15u))
+    return VTC_ERR_INVALID_ARG;
+  return vtc::launch_kv_append(*params, num_seqs, k_new, v_new, cu_new_lens, max_new_len, k_cache, v_cache,
+                               block_table, seq_lens, static_cast<hipStream_t>(hip_stream));
 }
 
 int vtc_debug_gather_slots(const vtc_attn_params* params, int32_t num_seqs, const int32_t* block_table,

@@ -171,6 +171,16 @@ int launch_prefill(const vtc_attn_params& p, int32_t num_seqs, const void* q, co
 int launch_counter_update(int64_t* counters, int32_t num_clients, const int32_t* client_ids,
                           const int32_t* n_in, const int32_t* n_out, int32_t n, int64_t w_p, int64_t w_q,
                           hipStream_t stream);
+int launch_counter_update_cost(int64_t* counters, int32_t num_clients, const int32_t* client_ids,
+                               const int32_t* p_old, const int32_t* q_old, const int32_t* p_new,
+                               const int32_t* q_new, int32_t n, const vtc_cost_poly& h,
+                               const int64_t* client_multiplier, hipStream_t stream);
+int launch_counter_update_predicted(int64_t* counters, int32_t num_clients, const int32_t* client_ids,
+                                    const int32_t* n_output, const int32_t* n_predicted, const int32_t* finished,
+                                    int32_t n, int64_t w_q, hipStream_t stream);
+int launch_kv_append(const vtc_attn_params& p, int32_t num_seqs, const void* k_new, const void* v_new,
+                     const int32_t* cu_new_lens, int32_t max_new_len, void* k_cache, void* v_cache,
+                     const int32_t* block_table, const int32_t* seq_lens, hipStream_t stream);
 int launch_gather_slots(const vtc_attn_params& p, int32_t num_seqs, const int32_t* block_table,
                         const int32_t* seq_lens, const int32_t* cu_out, int32_t max_seq_len,
                         int32_t* slots_out, hipStream_t stream);

@@ -28,14 +28,15 @@ def _declared_symbols():
 
 def test_every_declared_symbol_is_exported(lib):
     names = _declared_symbols()
-    assert {"vtc_attn_decode", "vtc_attn_prefill_chunk", "vtc_counter_update", "vtc_attn_workspace_bytes",
+    assert {"vtc_attn_decode", "vtc_attn_decode_profiled", "vtc_attn_prefill_chunk", "vtc_counter_update",
+            "vtc_counter_update_cost", "vtc_counter_update_predicted", "vtc_kv_append", "vtc_attn_workspace_bytes",
             "vtc_debug_gather_slots", "vtc_strerror", "vtc_version"} <= set(names)
     for name in names:
         assert getattr(lib, name) is not None
 
 
 def test_version_and_strerror(lib):
-    assert vtc.vtc_version() >= 100
+    assert vtc.vtc_version() >= 200
     for code in (0, -1, -2, -3, -4, -99):
         assert isinstance(vtc.vtc_strerror(code), str) and vtc.vtc_strerror(code)
     assert vtc.vtc_strerror(0) == "success"
@@ -52,12 +53,15 @@ def test_workspace_bytes_is_host_arithmetic(lib):
     p = good_params()
     small = vtc.vtc_attn_workspace_bytes(p, 8, 256)
     big = vtc.vtc_attn_workspace_bytes(p, 512, 4096)
-    full = vtc.vtc_attn_workspace_bytes(p, 512, 0)
-    assert 0 < small < big == full
-    assert vtc.vtc_attn_workspace_bytes(p, 512, 10 ** 9) == full        # clamped to the table capacity
+    assert 0 < small < big
+    # the footprint does not grow with the context length: a wave owns at most two partial results
+    assert vtc.vtc_attn_workspace_bytes(p, 512, 0) == big == vtc.vtc_attn_workspace_bytes(p, 512, 10 ** 9)
     assert big % 256 == 0
-    # at least one fp32 partial (128 floats + m, l) per (chunk of <= 256 tokens, q head)
-    assert big >= 512 * (4096 // 256) * 32 * (128 + 2) * 4
+    # room for two fp32 partials (128 floats + m, l) per q head of the group for every wave of the largest launch
+    assert big >= 2 * 8192 * 4 * (128 + 2) * 4
+    assert big < 64 << 20
+    mha = vtc.vtc_attn_workspace_bytes(good_params(num_q_heads=32, num_kv_heads=32), 512, 4096)
+    assert mha < big                                   # fewer q heads share a KV head
     assert vtc.vtc_attn_workspace_bytes(good_params(head_dim=64), 8, 256) == 0
     assert lib.vtc_attn_workspace_bytes(None, 8, 256) == 0
 
@@ -104,6 +108,21 @@ def test_null_pointers_sizes_alignment_and_workspace(lib):
     assert lib.vtc_counter_update(a, -1, a, a, a, 8, 1, 2, None) == -1
     assert lib.vtc_counter_update(a, 4, a, a, a, -8, 1, 2, None) == -1
     assert lib.vtc_counter_update(None, 4, None, None, None, 0, 1, 2, None) == 0
+
+    h = vtc.CostPoly(0, 1, 2, 0, 0, 0)
+    assert lib.vtc_counter_update_cost(a, 4, a, a, a, a, a, 8, None, None, None) == -1
+    assert lib.vtc_counter_update_cost(a, 4, a, a, a, None, a, 8, ctypes.byref(h), None, None) == -1
+    assert lib.vtc_counter_update_cost(None, 4, a, a, a, a, a, 8, ctypes.byref(h), None, None) == -1
+    assert lib.vtc_counter_update_cost(a, 4, a, a, a, a, a, -1, ctypes.byref(h), None, None) == -1
+    assert lib.vtc_counter_update_cost(None, 4, None, None, None, None, None, 0, ctypes.byref(h), None, None) == 0
+    assert lib.vtc_counter_update_predicted(a, 4, a, a, None, a, 8, 2, None) == -1
+    assert lib.vtc_counter_update_predicted(a, -4, a, a, a, a, 8, 2, None) == -1
+    assert lib.vtc_counter_update_predicted(None, 4, None, None, None, None, 0, 2, None) == 0
+    assert lib.vtc_kv_append(ctypes.byref(p), 2, a, a, a, 1, a, a, a, None, None) == -1
+    assert lib.vtc_kv_append(ctypes.byref(p), 2, a, ctypes.c_void_p(4104), a, 1, a, a, a, a, None) == -1
+    assert lib.vtc_kv_append(ctypes.byref(p), 2, a, a, a, -1, a, a, a, a, None) == -1
+    assert lib.vtc_kv_append(ctypes.byref(p), 0, None, None, None, 0, None, None, None, None, None) == 0
+    assert lib.vtc_kv_append(ctypes.byref(good_params(head_dim=64)), 2, a, a, a, 1, a, a, a, a, None) == -2
 
     assert lib.vtc_debug_gather_slots(ctypes.byref(p), 2, a, a, a, -1, a, None) == -1
     assert lib.vtc_debug_gather_slots(ctypes.byref(p), 2, None, a, a, 5, a, None) == -1
