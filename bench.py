@@ -125,6 +125,48 @@ def cpu_baseline(st, scale, sample_requests):
     }
 
 
+def aux_kernel_times(torch, vtc, st, params, stream, reps: int = 50):
+    """Average GPU time (us) of the small kernels around attention, on this batch: appending the batch's
+    current tokens to the cache, and the three counter updates.  Latency-bound; reported, not rooflined."""
+    b = st.batch
+    sh = b.shape
+    n = b.num_decode
+    dev = st.q.device
+    k_new = torch.randn((n, sh.num_kv_heads, sh.head_dim), device=dev).to(st.k_cache.dtype)
+    v_new = torch.randn((n, sh.num_kv_heads, sh.head_dim), device=dev).to(st.k_cache.dtype)
+    cu = torch.arange(n + 1, dtype=torch.int32, device=dev)
+    ids = st.cu_client_ids[:n].contiguous()
+    zeros = torch.zeros(n, dtype=torch.int32, device=dev)
+    ones = torch.ones(n, dtype=torch.int32, device=dev)
+    n_in = (st.seq_lens - 1).clamp(min=0).to(torch.int32)
+    h = vtc.CostPoly(11460, 2100, 1000, 0, 40, 32)
+    scratch = st.counters.clone()
+
+    def timed(fn):
+        with torch.cuda.stream(stream):
+            for _ in range(5):
+                fn()
+            a, e = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            a.record(stream)
+            for _ in range(reps):
+                fn()
+            e.record(stream)
+            e.synchronize()
+        return round(a.elapsed_time(e) * 1e3 / reps, 2)
+
+    # the append rewrites the rows of the current tokens with fresh values; it runs after all attention timing
+    return {
+        "kv_append_current_tokens": timed(lambda: vtc.vtc_kv_append(params, k_new, v_new, cu, 1, st.k_cache,
+                                                                    st.v_cache, st.block_table, st.seq_lens)),
+        "counter_update": timed(lambda: vtc.vtc_counter_update(scratch, ids, None, ones, b.w_p, b.w_q)),
+        "counter_update_cost_profiled": timed(lambda: vtc.vtc_counter_update_cost(scratch, ids, n_in, zeros, n_in,
+                                                                                  ones, h)),
+        "counter_update_predicted": timed(lambda: vtc.vtc_counter_update_predicted(scratch, ids, ones, zeros, zeros,
+                                                                                   b.w_q)),
+        "note": "back-to-back launches on one stream, average per launch",
+    }
+
+
 def main() -> int:
     args = parse_args()
     if args.gpus != 1:
@@ -252,6 +294,7 @@ def main() -> int:
             "unit": "TFLOP/s",
             "frac": round(batch.prefill_flops / (pf_avg * 1e-3) / 1e12 / MFMA_PEAK_TFLOPS, 4),
         }
+    line["aux_kernels_us"] = aux_kernel_times(torch, vtc, st, params, stream)
     if not args.no_cpu_baseline:
         line["cpu_baseline"] = cpu_baseline(st, scale, args.cpu_sample_requests)
         line["cpu_baseline"]["value"] = round(line["cpu_baseline"]["value"], 4)

@@ -126,78 +126,6 @@ __global__ __launch_bounds__(kPlanThreads) void decode_plan_kernel(const int32_t
 }
 
 // ---------------------------------------------------------------- attend ----
-template <int G>
-struct RowState {
-  float m[G];        // running max of the scaled logits (log2 domain)
-  float l[G];        // running sum of exp2(logit - m)
-  float acc[G][8];   // running sum of exp2(logit - m) * v, dims 8*sub .. 8*sub+7
-  __device__ __forceinline__ void reset() {
-#pragma unroll
-    for (int g = 0; g < G; ++g) {
-      m[g] = -INFINITY;
-      l[g] = 0.f;
-#pragma unroll
-      for (int e = 0; e < 8; ++e) acc[g][e] = 0.f;
-    }
-  }
-};
-
-// Process one K/V block (16 tokens).  `nvalid` < 16 marks a ragged last block:
-// tokens >= nvalid are excluded and their (possibly garbage) V rows zeroed.
-template <typename T, int G, bool kTail>
-__device__ __forceinline__ void block_update(RowState<G>& st, const u32x4 (&q)[G], const u32x4 (&k)[4],
-                                             u32x4 (&v)[4], float scale2, int row, int nvalid) {
-  float s[G][4];
-#pragma unroll
-  for (int i = 0; i < 4; ++i) {
-#pragma unroll
-    for (int g = 0; g < G; ++g) {
-      float d = 0.f;
-#pragma unroll
-      for (int w = 0; w < 4; ++w) d = dot2<T>(q[g][w], k[i][w], d);
-      s[g][i] = row16_allreduce_sum(d) * scale2;
-    }
-  }
-  if (kTail) {
-#pragma unroll
-    for (int i = 0; i < 4; ++i) {
-      const bool ok = 4 * i + row < nvalid;
-#pragma unroll
-      for (int g = 0; g < G; ++g) s[g][i] = ok ? s[g][i] : -INFINITY;
-      if (!ok) v[i] = u32x4{0u, 0u, 0u, 0u};
-    }
-  }
-  float p[G][4];
-#pragma unroll
-  for (int g = 0; g < G; ++g) {
-    const float mx = fmaxf(fmaxf(s[g][0], s[g][1]), fmaxf(s[g][2], s[g][3]));
-    const float m_new = fmaxf(st.m[g], mx);
-    // a row that has seen no valid token yet keeps m = -inf; subtract 0 instead so
-    // that exp2 yields 0 rather than NaN
-    const float m_sub = (kTail && m_new == -INFINITY) ? 0.f : m_new;
-    const float alpha = fast_exp2(st.m[g] - m_sub);
-#pragma unroll
-    for (int i = 0; i < 4; ++i) p[g][i] = fast_exp2(s[g][i] - m_sub);
-    st.l[g] = st.l[g] * alpha + ((p[g][0] + p[g][1]) + (p[g][2] + p[g][3]));
-#pragma unroll
-    for (int e = 0; e < 8; ++e) st.acc[g][e] *= alpha;
-    st.m[g] = m_new;
-  }
-#pragma unroll
-  for (int i = 0; i < 4; ++i) {
-#pragma unroll
-    for (int w = 0; w < 4; ++w) {
-      const float lo = lo_f32<T>(v[i][w]);
-      const float hi = hi_f32<T>(v[i][w]);
-#pragma unroll
-      for (int g = 0; g < G; ++g) {
-        st.acc[g][2 * w] = fmaf(p[g][i], lo, st.acc[g][2 * w]);
-        st.acc[g][2 * w + 1] = fmaf(p[g][i], hi, st.acc[g][2 * w + 1]);
-      }
-    }
-  }
-}
-
 // Load one 4 KiB tile (4 x 1 KiB across the wave).  `stride16` is kWave for a real tile; 0 turns the
 // four loads into re-reads of one 1 KiB line set (the throw-away prefetch at the end of a range).
 __device__ __forceinline__ void load_tile(u32x4 (&dst)[4], const uint16_t* __restrict__ tile, int lane, int stride16) {
@@ -212,6 +140,291 @@ __device__ __forceinline__ void load_tile(u32x4 (&dst)[4], const uint16_t* __res
   }
 }
 
+// Where a finished piece goes: the output row block of its (sequence, kv head) and its partial slot.
+struct PieceSink {
+  uint16_t* out_rows;   // out + (r * Hq + h * G) * 128: G consecutive rows of 128
+  float* part_acc;      // part_acc + slot0 * 128, slot0 = (wave * 2 + end) * G: G consecutive partials
+  float2* part_ml;      // part_ml + slot0
+};
+
+// ---- vector-ALU engine: lane = 16 * row + sub handles token 4i + row of load i, dims 8*sub..8*sub+7 ----
+template <typename T, int G>
+struct ValuEngine {
+  static constexpr int kQRegs = G;       // one 16-byte q slice per query head
+  static constexpr int kLdsElems = 0;
+  static constexpr int kMinWavesPerSimd = G == 1 ? 4 : (G == 2 ? 3 : (G == 4 ? 2 : 1));   // register budget
+  int row, sub;
+  float m[G];        // running max of the scaled logits (log2 domain), per 16-lane row
+  float l[G];        // running sum of exp2(logit - m)
+  float acc[G][8];   // running sum of exp2(logit - m) * v, dims 8*sub .. 8*sub+7
+
+  __device__ __forceinline__ void init(int lane, uint16_t*) {
+    row = lane >> 4;
+    sub = lane & 15;
+    reset();
+  }
+  __device__ __forceinline__ void reset() {
+#pragma unroll
+    for (int g = 0; g < G; ++g) {
+      m[g] = -INFINITY;
+      l[g] = 0.f;
+#pragma unroll
+      for (int e = 0; e < 8; ++e) acc[g][e] = 0.f;
+    }
+  }
+  // q_rows = q + (r * Hq + h * G) * 128
+  __device__ __forceinline__ void load_q(u32x4 (&dst)[kQRegs], const uint16_t* __restrict__ q_rows) const {
+#pragma unroll
+    for (int g = 0; g < G; ++g) dst[g] = *reinterpret_cast<const u32x4*>(q_rows + g * kHeadDim + sub * 8);
+  }
+
+  // One K/V block (16 tokens).  kTail: tokens >= nvalid are excluded and their (possibly garbage) V rows zeroed.
+  template <bool kTail>
+  __device__ __forceinline__ void block_t(const u32x4 (&q)[kQRegs], const u32x4 (&k)[4], u32x4 (&v)[4], float scale2,
+                                          int nvalid) {
+    float s[G][4];
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+#pragma unroll
+      for (int g = 0; g < G; ++g) {
+        float d = 0.f;
+#pragma unroll
+        for (int w = 0; w < 4; ++w) d = dot2<T>(q[g][w], k[i][w], d);
+        s[g][i] = row16_allreduce_sum(d) * scale2;
+      }
+    }
+    if (kTail) {
+#pragma unroll
+      for (int i = 0; i < 4; ++i) {
+        const bool ok = 4 * i + row < nvalid;
+#pragma unroll
+        for (int g = 0; g < G; ++g) s[g][i] = ok ? s[g][i] : -INFINITY;
+        if (!ok) v[i] = u32x4{0u, 0u, 0u, 0u};
+      }
+    }
+    float p[G][4];
+#pragma unroll
+    for (int g = 0; g < G; ++g) {
+      const float mx = fmaxf(fmaxf(s[g][0], s[g][1]), fmaxf(s[g][2], s[g][3]));
+      const float m_new = fmaxf(m[g], mx);
+      // a row that has seen no valid token yet keeps m = -inf; subtract 0 instead so
+      // that exp2 yields 0 rather than NaN
+      const float m_sub = (kTail && m_new == -INFINITY) ? 0.f : m_new;
+      const float alpha = fast_exp2(m[g] - m_sub);
+#pragma unroll
+      for (int i = 0; i < 4; ++i) p[g][i] = fast_exp2(s[g][i] - m_sub);
+      l[g] = l[g] * alpha + ((p[g][0] + p[g][1]) + (p[g][2] + p[g][3]));
+#pragma unroll
+      for (int e = 0; e < 8; ++e) acc[g][e] *= alpha;
+      m[g] = m_new;
+    }
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+#pragma unroll
+      for (int w = 0; w < 4; ++w) {
+        const float lo = lo_f32<T>(v[i][w]);
+        const float hi = hi_f32<T>(v[i][w]);
+#pragma unroll
+        for (int g = 0; g < G; ++g) {
+          acc[g][2 * w] = fmaf(p[g][i], lo, acc[g][2 * w]);
+          acc[g][2 * w + 1] = fmaf(p[g][i], hi, acc[g][2 * w + 1]);
+        }
+      }
+    }
+  }
+  __device__ __forceinline__ void block(const u32x4 (&q)[kQRegs], const u32x4 (&k)[4], u32x4 (&v)[4], float scale2,
+                                        int nvalid) {
+    if (nvalid < kBlockSize)
+      block_t<true>(q, k, v, scale2, nvalid);
+    else
+      block_t<false>(q, k, v, scale2, kBlockSize);
+  }
+
+  // Close a piece: merge the four 16-lane rows, write the output (whole sequence) or a partial, reset.
+  __device__ __forceinline__ void finish(bool whole, const PieceSink& sink) {
+#pragma unroll
+    for (int off = 16; off <= 32; off <<= 1) {
+#pragma unroll
+      for (int g = 0; g < G; ++g) {
+        const float m_o = __shfl_xor(m[g], off);
+        const float l_o = __shfl_xor(l[g], off);
+        const float m_n = fmaxf(m[g], m_o);
+        const float m_sub = m_n == -INFINITY ? 0.f : m_n;
+        const float a = fast_exp2(m[g] - m_sub);
+        const float b = fast_exp2(m_o - m_sub);
+        l[g] = l[g] * a + l_o * b;
+#pragma unroll
+        for (int e = 0; e < 8; ++e) acc[g][e] = acc[g][e] * a + __shfl_xor(acc[g][e], off) * b;
+        m[g] = m_n;
+      }
+    }
+    if (row == 0) {
+#pragma unroll
+      for (int g = 0; g < G; ++g) {
+        if (whole) {
+          const float inv = 1.f / l[g];
+          u32x4 o;
+#pragma unroll
+          for (int w2 = 0; w2 < 4; ++w2) o[w2] = pack2<T>(acc[g][2 * w2] * inv, acc[g][2 * w2 + 1] * inv);
+          *reinterpret_cast<u32x4*>(sink.out_rows + g * kHeadDim + sub * 8) = o;
+        } else {
+          float4* dst = reinterpret_cast<float4*>(sink.part_acc + g * kPartialFloats + sub * 8);
+          dst[0] = make_float4(acc[g][0], acc[g][1], acc[g][2], acc[g][3]);
+          dst[1] = make_float4(acc[g][4], acc[g][5], acc[g][6], acc[g][7]);
+          if (sub == 0) sink.part_ml[g] = make_float2(m[g], l[g]);
+        }
+      }
+    }
+    reset();
+  }
+};
+
+// ---- matrix-core engine for grouped-query attention (2 <= G <= 16) --------------------------------------
+// With G query heads per KV head the vector-ALU engine spends ~110 instructions per head and block and
+// becomes ALU-bound (measured: 75 % VALU busy at G = 4).  Here a block is two small matrix products on the
+// G x 16-token problem, padded to 16 x 16:
+//   S^T[token][head] = K . Q^T     4 x v_mfma_f32_16x16x32   A = K rows (tile staged in LDS, 16-byte reads)
+//                                                            B = Q^T in registers
+//   O^T[dim][head]  += V^T . P^T   8 x v_mfma_f32_16x16x16   A = V^T via the transposing LDS read
+//                                                            B = P^T = the accumulator layout of S^T
+// lane = 16 * kg + j: j is the head (columns) or token/dim (rows), kg the contraction group.  Columns
+// j >= G are padding (they repeat head G-1 and are never written).
+template <typename T, int G>
+struct MfmaEngine {
+  static_assert(G >= 2 && G <= 16, "group size");
+  static constexpr int kQRegs = (G + 3) / 4;      // the G q rows (256 B each) as 16 bytes per lane, 4 rows per register set
+  static constexpr int kPitchK = kHeadDim + 8;    // 272 B rows: conflict-free 16-byte row reads
+  static constexpr int kPitchV = kHeadDim + 16;   // 288 B rows: the 16-row x 32-byte transposing reads use every bank twice
+  static constexpr int kPitchQ = kHeadDim + 8;
+  static constexpr int kLdsElems = kBlockSize * (kPitchK + kPitchV) + 4 * kQRegs * kPitchQ;
+  static constexpr int kMinWavesPerSimd = VTC_DECODE_MFMA_WAVES_PER_SIMD;   // register budget = 512 / this
+  using f32x4 = float __attribute__((ext_vector_type(4)));
+  using f16x8 = _Float16 __attribute__((ext_vector_type(8)));
+  using bf16x8 = __bf16 __attribute__((ext_vector_type(8)));
+  using f16x4 = _Float16 __attribute__((ext_vector_type(4)));
+  using s16x4 = short __attribute__((ext_vector_type(4)));
+  using u32x2 = uint32_t __attribute__((ext_vector_type(2)));
+
+  int row, sub;      // staging layout of a loaded tile: token 4i + row, dims 8*sub..
+  int j, kg;         // matrix layout
+  uint16_t* k_lds;
+  uint16_t* v_lds;
+  uint16_t* q_lds;
+  float m, l;        // softmax state of head j (m identical in the 4 lane groups, l partial per group)
+  f32x4 acc[8];      // O^T: dims 16*db + 4*kg + v of head j
+
+  __device__ __forceinline__ void init(int lane, uint16_t* lds) {
+    row = kg = lane >> 4;
+    sub = j = lane & 15;
+    k_lds = lds;
+    v_lds = lds + kBlockSize * kPitchK;
+    q_lds = v_lds + kBlockSize * kPitchV;
+    reset();
+  }
+  __device__ __forceinline__ void reset() {
+    m = -INFINITY;
+    l = 0.f;
+#pragma unroll
+    for (int db = 0; db < 8; ++db) acc[db] = f32x4{0.f, 0.f, 0.f, 0.f};
+  }
+  // The q rows are fetched like a tile (lane = 16 * row + sub: head 4i + row, dims 8*sub..) and turned into the
+  // Q^T operand through LDS when the block is consumed; heads >= G repeat head G-1.
+  __device__ __forceinline__ void load_q(u32x4 (&dst)[kQRegs], const uint16_t* __restrict__ q_rows) const {
+#pragma unroll
+    for (int i = 0; i < kQRegs; ++i)
+      dst[i] = *reinterpret_cast<const u32x4*>(q_rows + min(4 * i + row, G - 1) * kHeadDim + sub * 8);
+  }
+
+  static __device__ __forceinline__ f32x4 mfma_qk(u32x4 a, u32x4 b, f32x4 c) {
+    if constexpr (__is_same(T, F16))
+      return __builtin_amdgcn_mfma_f32_16x16x32_f16(__builtin_bit_cast(f16x8, a), __builtin_bit_cast(f16x8, b), c, 0, 0, 0);
+    else
+      return __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, a), __builtin_bit_cast(bf16x8, b), c, 0, 0, 0);
+  }
+  static __device__ __forceinline__ f32x4 mfma_pv(u32x2 a, u32x2 b, f32x4 c) {
+    if constexpr (__is_same(T, F16))
+      return __builtin_amdgcn_mfma_f32_16x16x16f16(__builtin_bit_cast(f16x4, a), __builtin_bit_cast(f16x4, b), c, 0, 0, 0);
+    else
+      return __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(__builtin_bit_cast(s16x4, a), __builtin_bit_cast(s16x4, b), c, 0, 0, 0);
+  }
+
+  __device__ __forceinline__ void block(const u32x4 (&q)[kQRegs], const u32x4 (&k)[4], u32x4 (&v)[4], float scale2,
+                                        int nvalid) {
+    const bool tail = nvalid < kBlockSize;
+    // stage the tile row-major in this wave's LDS patch (the wave's LDS operations complete in order)
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      if (tail && 4 * i + row >= nvalid) v[i] = u32x4{0u, 0u, 0u, 0u};   // garbage rows must not meet a zero weight as NaN
+      *reinterpret_cast<u32x4*>(&k_lds[(4 * i + row) * kPitchK + sub * 8]) = k[i];
+      *reinterpret_cast<u32x4*>(&v_lds[(4 * i + row) * kPitchV + sub * 8]) = v[i];
+    }
+#pragma unroll
+    for (int i = 0; i < kQRegs; ++i) *reinterpret_cast<u32x4*>(&q_lds[(4 * i + row) * kPitchQ + sub * 8]) = q[i];
+    // S^T[token 4*kg + v][head j]
+    f32x4 s = f32x4{0.f, 0.f, 0.f, 0.f};
+    const uint16_t* qrow = q_lds + min(j, 4 * kQRegs - 1) * kPitchQ + kg * 8;
+#pragma unroll
+    for (int ks = 0; ks < 4; ++ks) {
+      const u32x4 kf = *reinterpret_cast<const u32x4*>(&k_lds[j * kPitchK + ks * 32 + kg * 8]);
+      const u32x4 qf = *reinterpret_cast<const u32x4*>(qrow + ks * 32);
+      s = mfma_qk(kf, qf, s);
+    }
+    float mx = -INFINITY;
+#pragma unroll
+    for (int e = 0; e < 4; ++e) {
+      s[e] *= scale2;
+      if (tail && 4 * kg + e >= nvalid) s[e] = -INFINITY;
+      mx = fmaxf(mx, s[e]);
+    }
+    mx = fmaxf(mx, __shfl_xor(mx, 16));
+    mx = fmaxf(mx, __shfl_xor(mx, 32));
+    const float m_new = fmaxf(m, mx);
+    const float m_sub = m_new == -INFINITY ? 0.f : m_new;
+    const float alpha = fast_exp2(m - m_sub);
+    m = m_new;
+    float p[4];
+#pragma unroll
+    for (int e = 0; e < 4; ++e) p[e] = fast_exp2(s[e] - m_sub);
+    l = l * alpha + ((p[0] + p[1]) + (p[2] + p[3]));
+    if (__builtin_amdgcn_ballot_w64(alpha != 1.f) != 0ull) {          // skip the rescale when no head's maximum moved
+#pragma unroll
+      for (int db = 0; db < 8; ++db) acc[db] *= alpha;
+    }
+    const u32x2 pb = u32x2{pack2<T>(p[0], p[1]), pack2<T>(p[2], p[3])};   // P^T: tokens 4*kg + 0..3 of head j
+    // O^T[dim][head] += V^T . P^T; lane j of group kg addresses token 4*kg + j/4, dims 4*(j%4).. of each 16-dim block
+    typedef __attribute__((address_space(3))) s16x4 lds_s16x4;
+    const uint16_t* vrow = v_lds + (4 * kg + (j >> 2)) * kPitchV + 4 * (j & 3);
+#pragma unroll
+    for (int db = 0; db < 8; ++db) {
+      const s16x4 vt = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4*)(vrow + db * 16));
+      acc[db] = mfma_pv(__builtin_bit_cast(u32x2, vt), pb, acc[db]);
+    }
+  }
+
+  __device__ __forceinline__ void finish(bool whole, const PieceSink& sink) {
+    float l_tot = l + __shfl_xor(l, 16);
+    l_tot += __shfl_xor(l_tot, 32);
+    if (j < G) {
+      if (whole) {
+        const float inv = 1.f / l_tot;
+        uint16_t* dst = sink.out_rows + j * kHeadDim + 4 * kg;
+#pragma unroll
+        for (int db = 0; db < 8; ++db) {
+          const u32x2 o = u32x2{pack2<T>(acc[db][0] * inv, acc[db][1] * inv), pack2<T>(acc[db][2] * inv, acc[db][3] * inv)};
+          *reinterpret_cast<u32x2*>(dst + db * 16) = o;
+        }
+      } else {
+        float* dst = sink.part_acc + j * kPartialFloats + 4 * kg;
+#pragma unroll
+        for (int db = 0; db < 8; ++db)
+          *reinterpret_cast<float4*>(dst + db * 16) = make_float4(acc[db][0], acc[db][1], acc[db][2], acc[db][3]);
+        if (kg == 0) sink.part_ml[j] = make_float2(m, l_tot);
+      }
+    }
+    reset();
+  }
+};
+
 // A position in the stream: which block, and where its K/V tile lives.
 struct StreamPos {
   int r, h, b;       // sequence, kv head, block index inside the sequence
@@ -220,15 +433,15 @@ struct StreamPos {
   size_t off;        // element offset of the (block, head) tile in k_cache / v_cache
 };
 
-template <typename T, int G>
-__global__ __launch_bounds__(kWave) void decode_attend_kernel(
+template <typename T, int G, typename Engine>
+__global__ __launch_bounds__(kWave, Engine::kMinWavesPerSimd) void decode_attend_kernel(
     const uint16_t* __restrict__ q, const uint16_t* __restrict__ k_cache, const uint16_t* __restrict__ v_cache,
     const int32_t* __restrict__ block_table, const int32_t* __restrict__ seq_lens, uint16_t* __restrict__ out,
     const int4* __restrict__ wave_desc, float2* __restrict__ part_ml, float* __restrict__ part_acc,
     int32_t num_kv_heads, int32_t max_blocks_per_seq, float scale2) {
+  constexpr int kQRegs = Engine::kQRegs;
+  __shared__ __attribute__((aligned(16))) uint16_t lds[Engine::kLdsElems > 0 ? Engine::kLdsElems : 8];
   const int lane = threadIdx.x;
-  const int row = lane >> 4;
-  const int sub = lane & 15;
   const int num_q_heads = num_kv_heads * G;
   const int max_tokens = max_blocks_per_seq * kBlockSize;
   const int wave = blockIdx.x;
@@ -257,11 +470,7 @@ __global__ __launch_bounds__(kWave) void decode_attend_kernel(
     }
     locate(p);
   };
-  auto load_q = [&](u32x4 (&dst)[G], const StreamPos& p) {
-#pragma unroll
-    for (int g = 0; g < G; ++g)
-      dst[g] = *reinterpret_cast<const u32x4*>(q + ((size_t)p.r * num_q_heads + p.h * G + g) * kHeadDim + sub * 8);
-  };
+  auto q_rows = [&](const StreamPos& p) { return q + ((size_t)p.r * num_q_heads + p.h * G) * kHeadDim; };
 
   // cur: the block being consumed; nxt: the block whose loads are in flight; far: one further, so
   // that its (scalar) block-table lookup is never waited for between a tile's loads and their use.
@@ -279,81 +488,44 @@ __global__ __launch_bounds__(kWave) void decode_attend_kernel(
   }
   if (n_blocks > 2) step(far);
 
-  RowState<G> st;
-  st.reset();
+  Engine eng;
+  eng.init(lane, lds);
   int piece_lo = cur.b;                    // first block of the current piece
 
   // Two register sets (q, K tile, V tile), used alternately.  The q rows travel with the
   // tiles, so a set always holds the query of the block it holds.
-  u32x4 qa[G], ka[4], va[4], qb[G], kb[4], vb[4];
-  load_q(qa, cur);
+  u32x4 qa[kQRegs], ka[4], va[4], qb[kQRegs], kb[4], vb[4];
+  eng.load_q(qa, q_rows(cur));
   load_tile(ka, k_cache + cur.off, lane, kWave);
   load_tile(va, v_cache + cur.off, lane, kWave);
   // where the prefetch goes when there is no next block: 1 KiB of the (cache-resident) range table
   const uint16_t* const dummy = reinterpret_cast<const uint16_t*>(wave_desc);
 
   // Consume the block at `cur` from (qreg, kx, vx); close the piece if it ends here.
-  auto consume = [&](const u32x4 (&qreg)[G], u32x4 (&kx)[4], u32x4 (&vx)[4], bool last_of_range) {
+  auto consume = [&](const u32x4 (&qreg)[kQRegs], u32x4 (&kx)[4], u32x4 (&vx)[4], bool last_of_range) {
     const bool last_of_seq = cur.b + 1 == cur.nb;
     const int nvalid = last_of_seq ? cur.s_len - cur.b * kBlockSize : kBlockSize;
-    if (nvalid < kBlockSize)
-      block_update<T, G, true>(st, qreg, kx, vx, scale2, row, nvalid);
-    else
-      block_update<T, G, false>(st, qreg, kx, vx, scale2, row, kBlockSize);
+    eng.block(qreg, kx, vx, scale2, nvalid);
     if (!(last_of_seq || last_of_range)) return;
-
-    // merge the four 16-lane rows (lanes l, l^16, l^32, l^48 hold the same dims)
-#pragma unroll
-    for (int off = 16; off <= 32; off <<= 1) {
-#pragma unroll
-      for (int g = 0; g < G; ++g) {
-        const float m_o = __shfl_xor(st.m[g], off);
-        const float l_o = __shfl_xor(st.l[g], off);
-        const float m_n = fmaxf(st.m[g], m_o);
-        const float m_sub = m_n == -INFINITY ? 0.f : m_n;
-        const float a = fast_exp2(st.m[g] - m_sub);
-        const float b = fast_exp2(m_o - m_sub);
-        st.l[g] = st.l[g] * a + l_o * b;
-#pragma unroll
-        for (int e = 0; e < 8; ++e) st.acc[g][e] = st.acc[g][e] * a + __shfl_xor(st.acc[g][e], off) * b;
-        st.m[g] = m_n;
-      }
-    }
     const bool whole = piece_lo == 0 && last_of_seq;     // the piece is the entire sequence
-    if (row == 0) {
-#pragma unroll
-      for (int g = 0; g < G; ++g) {
-        if (whole) {
-          const float inv = 1.f / st.l[g];
-          u32x4 o;
-#pragma unroll
-          for (int w2 = 0; w2 < 4; ++w2) o[w2] = pack2<T>(st.acc[g][2 * w2] * inv, st.acc[g][2 * w2 + 1] * inv);
-          *reinterpret_cast<u32x4*>(out + ((size_t)cur.r * num_q_heads + cur.h * G + g) * kHeadDim + sub * 8) = o;
-        } else {
-          // slot 0: the piece cut at the start of this wave's range; slot 1: the one cut at its end
-          const size_t pi = ((size_t)wave * 2 + (piece_lo == 0 ? 1 : 0)) * G + g;
-          float4* dst = reinterpret_cast<float4*>(part_acc + pi * kPartialFloats + sub * 8);
-          dst[0] = make_float4(st.acc[g][0], st.acc[g][1], st.acc[g][2], st.acc[g][3]);
-          dst[1] = make_float4(st.acc[g][4], st.acc[g][5], st.acc[g][6], st.acc[g][7]);
-          if (sub == 0) part_ml[pi] = make_float2(st.m[g], st.l[g]);
-        }
-      }
-    }
-    st.reset();                             // a new (r, h) starts with the next block
-    piece_lo = 0;
+    // partial slot 0: the piece cut at the start of this wave's range; slot 1: the one cut at its end
+    const size_t slot0 = ((size_t)wave * 2 + (piece_lo == 0 ? 1 : 0)) * G;
+    eng.finish(whole, PieceSink{out + ((size_t)cur.r * num_q_heads + cur.h * G) * kHeadDim,
+                                part_acc + slot0 * kPartialFloats, part_ml + slot0});
+    piece_lo = 0;                           // a new (r, h) starts with the next block
   };
 
   // The prefetch of the next block is unconditional (no branch around the loads, so the
   // hardware load counter stays exact and a tile's wait never covers the loads issued after
   // it).  On the last block of the range it is pointed at 1 KiB that is already in cache and
-  // its result is dropped.  q is re-read with every block for the same reason (a 256-byte
-  // row that stays in cache); it only changes when the next block starts a new (r, h).
+  // its result is dropped.  q is re-read with every block for the same reason (256-byte
+  // rows that stay in cache); it only changes when the next block starts a new (r, h).
   int i = 0;
   while (true) {
     // -- even step: consume set a, prefetch into set b
     {
       const bool more = i + 1 < n_blocks;
-      load_q(qb, nxt);
+      eng.load_q(qb, q_rows(nxt));
       load_tile(kb, more ? k_cache + nxt.off : dummy, lane, more ? kWave : 0);
       load_tile(vb, more ? v_cache + nxt.off : dummy, lane, more ? kWave : 0);
     }
@@ -365,7 +537,7 @@ __global__ __launch_bounds__(kWave) void decode_attend_kernel(
     // -- odd step: consume set b, prefetch into set a
     {
       const bool more = i + 1 < n_blocks;
-      load_q(qa, nxt);
+      eng.load_q(qa, q_rows(nxt));
       load_tile(ka, more ? k_cache + nxt.off : dummy, lane, more ? kWave : 0);
       load_tile(va, more ? v_cache + nxt.off : dummy, lane, more ? kWave : 0);
     }
@@ -436,7 +608,7 @@ __global__ __launch_bounds__(kWave) void decode_merge_kernel(const DecodeHeader*
 }
 
 // -------------------------------------------------------------- launcher ----
-template <typename T, int G>
+template <typename T, int G, typename Engine>
 static int launch_typed(const vtc_attn_params& p, int32_t num_seqs, const void* q, const void* k_cache,
                         const void* v_cache, const int32_t* block_table, const int32_t* seq_lens, void* out,
                         void* workspace, hipStream_t stream, hipEvent_t ev_begin, hipEvent_t ev_end) {
@@ -454,7 +626,7 @@ static int launch_typed(const vtc_attn_params& p, int32_t num_seqs, const void* 
   static int waves_per_cu = 0;
   if (waves_per_cu == 0) {
     int occ = 0;
-    if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&occ, decode_attend_kernel<T, G>, kWave, 0) != hipSuccess || occ <= 0)
+    if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&occ, decode_attend_kernel<T, G, Engine>, kWave, 0) != hipSuccess || occ <= 0)
       occ = 8;
     waves_per_cu = occ < VTC_DECODE_WAVES_PER_CU ? occ : VTC_DECODE_WAVES_PER_CU;
   }
@@ -464,7 +636,7 @@ static int launch_typed(const vtc_attn_params& p, int32_t num_seqs, const void* 
   hipLaunchKernelGGL(decode_plan_kernel, dim3(1), dim3(kPlanThreads), 0, stream, seq_lens, num_seqs, p.num_kv_heads,
                      max_tokens, grid, header, seg_prefix, wave_desc);
   if (ev_begin && hipEventRecord(ev_begin, stream) != hipSuccess) return VTC_ERR_HIP;
-  hipLaunchKernelGGL((decode_attend_kernel<T, G>), dim3(grid), dim3(kWave), 0, stream,
+  hipLaunchKernelGGL((decode_attend_kernel<T, G, Engine>), dim3(grid), dim3(kWave), 0, stream,
                      static_cast<const uint16_t*>(q), static_cast<const uint16_t*>(k_cache),
                      static_cast<const uint16_t*>(v_cache), block_table, seq_lens, static_cast<uint16_t*>(out),
                      wave_desc, part_ml, part_acc, p.num_kv_heads, p.max_blocks_per_seq, p.scale * kLog2e);
@@ -475,15 +647,23 @@ static int launch_typed(const vtc_attn_params& p, int32_t num_seqs, const void* 
   return hipGetLastError() == hipSuccess ? VTC_OK : VTC_ERR_HIP;
 }
 
+#if VTC_DECODE_GQA_MFMA
+template <typename T, int G>
+using GqaEngine = MfmaEngine<T, G>;
+#else
+template <typename T, int G>
+using GqaEngine = ValuEngine<T, G>;
+#endif
+
 template <typename T>
 static int launch_group(const vtc_attn_params& p, int32_t num_seqs, const void* q, const void* k_cache,
                         const void* v_cache, const int32_t* block_table, const int32_t* seq_lens, void* out,
                         void* workspace, hipStream_t stream, hipEvent_t ev_begin, hipEvent_t ev_end) {
   switch (p.num_q_heads / p.num_kv_heads) {
-    case 1: return launch_typed<T, 1>(p, num_seqs, q, k_cache, v_cache, block_table, seq_lens, out, workspace, stream, ev_begin, ev_end);
-    case 2: return launch_typed<T, 2>(p, num_seqs, q, k_cache, v_cache, block_table, seq_lens, out, workspace, stream, ev_begin, ev_end);
-    case 4: return launch_typed<T, 4>(p, num_seqs, q, k_cache, v_cache, block_table, seq_lens, out, workspace, stream, ev_begin, ev_end);
-    case 8: return launch_typed<T, 8>(p, num_seqs, q, k_cache, v_cache, block_table, seq_lens, out, workspace, stream, ev_begin, ev_end);
+    case 1: return launch_typed<T, 1, ValuEngine<T, 1>>(p, num_seqs, q, k_cache, v_cache, block_table, seq_lens, out, workspace, stream, ev_begin, ev_end);
+    case 2: return launch_typed<T, 2, GqaEngine<T, 2>>(p, num_seqs, q, k_cache, v_cache, block_table, seq_lens, out, workspace, stream, ev_begin, ev_end);
+    case 4: return launch_typed<T, 4, GqaEngine<T, 4>>(p, num_seqs, q, k_cache, v_cache, block_table, seq_lens, out, workspace, stream, ev_begin, ev_end);
+    case 8: return launch_typed<T, 8, GqaEngine<T, 8>>(p, num_seqs, q, k_cache, v_cache, block_table, seq_lens, out, workspace, stream, ev_begin, ev_end);
     default: return VTC_ERR_UNSUPPORTED;
   }
 }

@@ -22,6 +22,12 @@ constexpr float kLog2e = 1.4426950408889634f;
 #ifndef VTC_DECODE_NT_LOADS
 #define VTC_DECODE_NT_LOADS 1            // 1: stream K/V with non-temporal loads
 #endif
+#ifndef VTC_DECODE_GQA_MFMA
+#define VTC_DECODE_GQA_MFMA 1            // 1: grouped-query decode runs its two small products on the matrix cores
+#endif
+#ifndef VTC_DECODE_MFMA_WAVES_PER_SIMD
+#define VTC_DECODE_MFMA_WAVES_PER_SIMD 2 // occupancy target of the matrix-core decode engine
+#endif
 #ifndef VTC_DECODE_MIN_BLOCKS_PER_WAVE
 #define VTC_DECODE_MIN_BLOCKS_PER_WAVE 2 // small batches use fewer waves rather than shorter ranges
 #endif
@@ -80,11 +86,11 @@ __device__ __forceinline__ float hi_f32<F16>(uint32_t w) {
 }
 template <>
 __device__ __forceinline__ float lo_f32<BF16>(uint32_t w) {
-  return __builtin_bit_cast(float, w << 16);
+  return (float)__builtin_bit_cast(bf16x2, w)[0];     // lets the compiler fold the widening into v_fma_mix_f32_bf16
 }
 template <>
 __device__ __forceinline__ float hi_f32<BF16>(uint32_t w) {
-  return __builtin_bit_cast(float, w & 0xffff0000u);
+  return (float)__builtin_bit_cast(bf16x2, w)[1];
 }
 
 // Round two floats to the storage type (nearest even) and pack them.
