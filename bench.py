@@ -7,7 +7,7 @@ A step is one pass of the hot path over one synthetic batch that is already
 resident in HBM: decode attention over the paged KV cache of every running
 request, the prefill-chunk attention of newly admitted prompts when the
 workload has any (cfg5), and one virtual-token-counter update for the whole
-batch.  Prints ONE JSON line: whole-step KV GB/s as ``value``, plus the
+batch (carried by the decode call's last launch: ``vtc_step_decode``).  Prints ONE JSON line: whole-step KV GB/s as ``value``, plus the
 roofline of the dominant kernel (decode attention, HBM-bound; its duration is
 measured with HIP events recorded on the launch stream right around that
 kernel) and the CPU oracle timed on a bounded sample of the same workload.
@@ -33,7 +33,7 @@ EVENT_EVERY = 5                # steps between two kernel-level HIP event pairs
 # by the copy-kernel calibration (profiles/decode_attend_cfg3_hbm_bytes.md).  Valid only for the kernel
 # source the counters were taken with: keyed by the SHA-256 of the two files that define that kernel.
 DECODE_TRAFFIC_CFG3 = {
-    "5ef23b54ff670014": 4062959223,
+    "fbcd4c0b21d88250": 4062403429,
 }
 
 
@@ -214,9 +214,10 @@ def main() -> int:
                                        st.pf_block_table, st.pf_seq_lens, out=pf_out)
             if pf_ev is not None:
                 pf_ev[1].record(stream)
-        vtc.vtc_attn_decode(params, st.q, st.k_cache, st.v_cache, st.block_table, st.seq_lens, out=out,
-                            workspace=ws, ev_begin=ev_b, ev_end=ev_e)
-        vtc.vtc_counter_update(st.counters, st.cu_client_ids, st.cu_n_in, st.cu_n_out, batch.w_p, batch.w_q)
+        # decode attention and the step's counter charge (decoding and newly prefilled requests) in one call
+        vtc.vtc_step_decode(params, st.q, st.k_cache, st.v_cache, st.block_table, st.seq_lens, st.counters,
+                            st.cu_client_ids, st.cu_n_in, st.cu_n_out, batch.w_p, batch.w_q, out=out, workspace=ws,
+                            ev_begin=ev_b, ev_end=ev_e)
 
     # The kernel-level events sit inside the timed region, on the launch stream, but only on every
     # EVENT_EVERY-th step: an event between two kernels costs a few microseconds of queue drain.

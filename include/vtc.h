@@ -97,9 +97,10 @@ size_t vtc_attn_workspace_bytes(const vtc_attn_params* params /*[host]*/, int32_
  *   out [device]        E [num_seqs, Hq, 128], written
  *   workspace [device]  >= vtc_attn_workspace_bytes(params, num_seqs, 0) bytes,
  *                       256-byte aligned, contents undefined before and after
- * num_seqs == 0 is a successful no-op.  The call enqueues a planning kernel, the
- * attention kernel and a merge kernel on hip_stream; two calls that share one
- * workspace must be ordered on the same stream.
+ * num_seqs == 0 is a successful no-op.  The call enqueues the attention kernel
+ * and a merge kernel on hip_stream (batches of more than 1024 sequences: a
+ * planning kernel first); two calls that share one workspace must be ordered on
+ * the same stream.
  */
 int vtc_attn_decode(const vtc_attn_params* params /*[host]*/, int32_t num_seqs, const void* q,
                     const void* k_cache, const void* v_cache, const int32_t* block_table,
@@ -118,6 +119,41 @@ int vtc_attn_decode_profiled(const vtc_attn_params* params /*[host]*/, int32_t n
                              const void* k_cache, const void* v_cache, const int32_t* block_table,
                              const int32_t* seq_lens, void* out, void* workspace,
                              size_t workspace_bytes, void* hip_stream, void* ev_begin, void* ev_end);
+
+/*
+ * One decode iteration of the execution stream of Algorithm 2 in a single call:
+ * forward_decode(B) (its attention part, exactly vtc_attn_decode) followed by
+ * the counter charge c_i += w_p * n_input_tokens + w_q * n_output_tokens summed
+ * over the requests of client i (exactly vtc_counter_update, declared below;
+ * for a pure decode step n_output_tokens is all ones and n_input_tokens NULL,
+ * i.e. c_i += w_q * |{r in B : client(r) = i}|).  The charge travels in the
+ * last launch of the attention, so the step costs no extra kernel launch.
+ *
+ * The two halves have separate request lists: attention runs over num_seqs
+ * sequences, the charge over n requests (a mixed step also charges the requests
+ * that were prefilled in the same iteration).  Arguments, layouts, clamping and
+ * error behaviour of each half are those of vtc_attn_decode and
+ * vtc_counter_update; all host-visible arguments of both halves are validated
+ * before anything is enqueued.  num_seqs == 0 performs the charge alone; n == 0
+ * or num_clients == 0 performs the attention alone.  The charge is not ordered
+ * against the attention inside the call; both are complete when the work
+ * enqueued by the call on hip_stream is.
+ */
+int vtc_step_decode(const vtc_attn_params* params /*[host]*/, int32_t num_seqs, const void* q,
+                    const void* k_cache, const void* v_cache, const int32_t* block_table,
+                    const int32_t* seq_lens, void* out, int64_t* counters, int32_t num_clients,
+                    const int32_t* client_ids, const int32_t* n_input_tokens,
+                    const int32_t* n_output_tokens, int32_t n, int64_t w_p, int64_t w_q, void* workspace,
+                    size_t workspace_bytes, void* hip_stream);
+
+/* Measurement hook: vtc_step_decode with the two events of vtc_attn_decode_profiled. */
+int vtc_step_decode_profiled(const vtc_attn_params* params /*[host]*/, int32_t num_seqs, const void* q,
+                             const void* k_cache, const void* v_cache, const int32_t* block_table,
+                             const int32_t* seq_lens, void* out, int64_t* counters, int32_t num_clients,
+                             const int32_t* client_ids, const int32_t* n_input_tokens,
+                             const int32_t* n_output_tokens, int32_t n, int64_t w_p, int64_t w_q,
+                             void* workspace, size_t workspace_bytes, void* hip_stream, void* ev_begin,
+                             void* ev_end);
 
 /*
  * Causal prefill-chunk attention -- the attention part of forward_prefill(B_new)

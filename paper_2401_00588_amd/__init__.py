@@ -22,6 +22,7 @@ from .binding import (  # noqa: F401
     vtc_counter_update_cost,
     vtc_counter_update_predicted,
     vtc_kv_append,
+    vtc_step_decode,
     vtc_debug_gather_slots,
     vtc_strerror,
     vtc_version,

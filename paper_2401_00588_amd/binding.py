@@ -72,6 +72,11 @@ def load_library() -> ctypes.CDLL:
     lib.vtc_attn_decode.argtypes = [P, i32, vp, vp, vp, vp, vp, vp, vp, sz, vp]
     lib.vtc_attn_decode_profiled.restype = ctypes.c_int
     lib.vtc_attn_decode_profiled.argtypes = [P, i32, vp, vp, vp, vp, vp, vp, vp, sz, vp, vp, vp]
+    lib.vtc_step_decode.restype = ctypes.c_int
+    lib.vtc_step_decode.argtypes = [P, i32, vp, vp, vp, vp, vp, vp, vp, i32, vp, vp, vp, i32, i64, i64, vp, sz, vp]
+    lib.vtc_step_decode_profiled.restype = ctypes.c_int
+    lib.vtc_step_decode_profiled.argtypes = [P, i32, vp, vp, vp, vp, vp, vp, vp, i32, vp, vp, vp, i32, i64, i64, vp,
+                                             sz, vp, vp, vp]
     lib.vtc_attn_prefill_chunk.restype = ctypes.c_int
     lib.vtc_attn_prefill_chunk.argtypes = [P, i32, vp, vp, i32, vp, vp, vp, vp, vp, vp, sz, vp]
     lib.vtc_counter_update.restype = ctypes.c_int
@@ -226,6 +231,61 @@ def vtc_attn_decode(params: AttnParams, q, k_cache, v_cache, block_table, seq_le
                                           ev_end.handle if ev_end else None)
     if rc != 0:
         raise VtcError(rc, "vtc_attn_decode")
+    return out
+
+
+def vtc_step_decode(params: AttnParams, q, k_cache, v_cache, block_table, seq_lens, counters, client_ids,
+                    n_input_tokens, n_output_tokens, w_p: int, w_q: int, out=None, workspace=None,
+                    ev_begin: Optional[HipEvent] = None, ev_end: Optional[HipEvent] = None):
+    """Decode attention plus the step's counter charge in one call (``counters`` is updated in place).
+
+    The attention arguments are those of ``vtc_attn_decode``, the charge arguments those of
+    ``vtc_counter_update``; ``client_ids`` may list more requests than ``seq_lens`` (a mixed step).
+    """
+    torch = _torch()
+    lib = load_library()
+    elt = _elt_dtype(params)
+    _check(q, "q", elt, 3)
+    _check(k_cache, "k_cache", elt, 4)
+    _check(v_cache, "v_cache", elt, 4)
+    _check(block_table, "block_table", torch.int32, 2)
+    _check(seq_lens, "seq_lens", torch.int32, 1)
+    n = int(seq_lens.shape[0])
+    if tuple(q.shape) != (n, params.num_q_heads, params.head_dim):
+        raise ValueError("q must be [num_seqs, num_q_heads, head_dim]")
+    if tuple(k_cache.shape[1:]) != (params.num_kv_heads, params.block_size, params.head_dim) or k_cache.shape != v_cache.shape:
+        raise ValueError("k_cache / v_cache must be [num_blocks, num_kv_heads, block_size, head_dim]")
+    if tuple(block_table.shape) != (n, params.max_blocks_per_seq):
+        raise ValueError("block_table must be [num_seqs, max_blocks_per_seq]")
+    if out is None:
+        out = torch.empty_like(q)
+    _check(out, "out", elt, 3)
+    if out.shape != q.shape:
+        raise ValueError("out must have the shape of q")
+    _check(counters, "counters", torch.int64, 1)
+    _check(client_ids, "client_ids", torch.int32, 1)
+    n_req = int(client_ids.shape[0])
+    for name, t in (("n_input_tokens", n_input_tokens), ("n_output_tokens", n_output_tokens)):
+        if t is not None:
+            _check(t, name, torch.int32, 1)
+            if t.shape[0] != n_req:
+                raise ValueError(f"{name} must have one entry per request")
+    need = vtc_attn_workspace_bytes(params, n, 0)
+    if workspace is None:
+        workspace = torch.empty(max(need, 256), dtype=torch.uint8, device=q.device)
+    _check(workspace, "workspace", torch.uint8, 1)
+    args = [ctypes.byref(params), n, q.data_ptr(), k_cache.data_ptr(), v_cache.data_ptr(), block_table.data_ptr(),
+            seq_lens.data_ptr(), out.data_ptr(), counters.data_ptr(), int(counters.shape[0]), client_ids.data_ptr(),
+            None if n_input_tokens is None else n_input_tokens.data_ptr(),
+            None if n_output_tokens is None else n_output_tokens.data_ptr(), n_req, int(w_p), int(w_q),
+            workspace.data_ptr(), workspace.numel(), _stream()]
+    if ev_begin is None and ev_end is None:
+        rc = lib.vtc_step_decode(*args)
+    else:
+        rc = lib.vtc_step_decode_profiled(*args, ev_begin.handle if ev_begin else None,
+                                          ev_end.handle if ev_end else None)
+    if rc != 0:
+        raise VtcError(rc, "vtc_step_decode")
     return out
 
 

@@ -24,7 +24,7 @@ int device_cu_count() {
 
 extern "C" {
 
-int vtc_version(void) { return 200; }
+int vtc_version(void) { return 210; }
 
 const char* vtc_strerror(int code) {
   switch (code) {
@@ -44,10 +44,10 @@ size_t vtc_attn_workspace_bytes(const vtc_attn_params* params, int32_t max_num_s
   return vtc::decode_workspace_layout(*params, max_num_seqs, max_seq_len).total_bytes;
 }
 
-int vtc_attn_decode_profiled(const vtc_attn_params* params, int32_t num_seqs, const void* q, const void* k_cache,
-                             const void* v_cache, const int32_t* block_table, const int32_t* seq_lens, void* out,
-                             void* workspace, size_t workspace_bytes, void* hip_stream, void* ev_begin,
-                             void* ev_end) {
+static int decode_common(const vtc_attn_params* params, int32_t num_seqs, const void* q, const void* k_cache,
+                         const void* v_cache, const int32_t* block_table, const int32_t* seq_lens, void* out,
+                         void* workspace, size_t workspace_bytes, void* hip_stream, void* ev_begin, void* ev_end,
+                         const vtc::CounterJob& job) {
   int rc = vtc::check_params(params);
   if (rc != VTC_OK) return rc;
   if (num_seqs < 0) return VTC_ERR_INVALID_ARG;
@@ -61,13 +61,55 @@ int vtc_attn_decode_profiled(const vtc_attn_params* params, int32_t num_seqs, co
     return VTC_ERR_WORKSPACE_TOO_SMALL;
   return vtc::launch_decode(*params, num_seqs, q, k_cache, v_cache, block_table, seq_lens, out, workspace,
                             static_cast<hipStream_t>(hip_stream), static_cast<hipEvent_t>(ev_begin),
-                            static_cast<hipEvent_t>(ev_end));
+                            static_cast<hipEvent_t>(ev_end), job);
+}
+
+int vtc_attn_decode_profiled(const vtc_attn_params* params, int32_t num_seqs, const void* q, const void* k_cache,
+                             const void* v_cache, const int32_t* block_table, const int32_t* seq_lens, void* out,
+                             void* workspace, size_t workspace_bytes, void* hip_stream, void* ev_begin,
+                             void* ev_end) {
+  return decode_common(params, num_seqs, q, k_cache, v_cache, block_table, seq_lens, out, workspace,
+                       workspace_bytes, hip_stream, ev_begin, ev_end, vtc::CounterJob{});
 }
 
 int vtc_attn_decode(const vtc_attn_params* params, int32_t num_seqs, const void* q, const void* k_cache,
                     const void* v_cache, const int32_t* block_table, const int32_t* seq_lens, void* out,
                     void* workspace, size_t workspace_bytes, void* hip_stream) {
-  return vtc_attn_decode_profiled(params, num_seqs, q, k_cache, v_cache, block_table, seq_lens, out, workspace,
+  return decode_common(params, num_seqs, q, k_cache, v_cache, block_table, seq_lens, out, workspace,
+                       workspace_bytes, hip_stream, nullptr, nullptr, vtc::CounterJob{});
+}
+
+int vtc_step_decode_profiled(const vtc_attn_params* params, int32_t num_seqs, const void* q, const void* k_cache,
+                             const void* v_cache, const int32_t* block_table, const int32_t* seq_lens, void* out,
+                             int64_t* counters, int32_t num_clients, const int32_t* client_ids,
+                             const int32_t* n_input_tokens, const int32_t* n_output_tokens, int32_t n,
+                             int64_t w_p, int64_t w_q, void* workspace, size_t workspace_bytes, void* hip_stream,
+                             void* ev_begin, void* ev_end) {
+  // every host-visible argument of both halves is checked before anything is enqueued
+  int rc = vtc::check_params(params);
+  if (rc != VTC_OK) return rc;
+  if (num_seqs < 0 || n < 0 || num_clients < 0) return VTC_ERR_INVALID_ARG;
+  const bool charge = n > 0 && num_clients > 0;
+  if (charge && (!counters || !client_ids)) return VTC_ERR_INVALID_ARG;
+  if (num_seqs == 0)                           // nothing to attend to: the charge alone
+    return charge ? vtc::launch_counter_update(counters, num_clients, client_ids, n_input_tokens, n_output_tokens, n,
+                                               w_p, w_q, static_cast<hipStream_t>(hip_stream))
+                  : VTC_OK;
+  vtc::CounterJob job{};
+  if (charge)
+    job = vtc::CounterJob{reinterpret_cast<unsigned long long*>(counters), num_clients, client_ids, n_input_tokens,
+                          n_output_tokens, n, (unsigned long long)w_p, (unsigned long long)w_q};
+  return decode_common(params, num_seqs, q, k_cache, v_cache, block_table, seq_lens, out, workspace,
+                       workspace_bytes, hip_stream, ev_begin, ev_end, job);
+}
+
+int vtc_step_decode(const vtc_attn_params* params, int32_t num_seqs, const void* q, const void* k_cache,
+                    const void* v_cache, const int32_t* block_table, const int32_t* seq_lens, void* out,
+                    int64_t* counters, int32_t num_clients, const int32_t* client_ids,
+                    const int32_t* n_input_tokens, const int32_t* n_output_tokens, int32_t n, int64_t w_p,
+                    int64_t w_q, void* workspace, size_t workspace_bytes, void* hip_stream) {
+  return vtc_step_decode_profiled(params, num_seqs, q, k_cache, v_cache, block_table, seq_lens, out, counters,
+                                  num_clients, client_ids, n_input_tokens, n_output_tokens, n, w_p, w_q, workspace,
                                   workspace_bytes, hip_stream, nullptr, nullptr);
 }
 

@@ -7,8 +7,11 @@
 // as r-major, then h, then b, and call that sequence of gtot blocks the *stream*.
 // The stream is cut into W equal ranges, one per resident wavefront, regardless of
 // where sequences begin and end, so every wave moves the same number of bytes:
-//   plan    one workgroup: blocks per sequence -> exclusive prefix; then for each
-//           wave the (r, h, b) at which its range starts and the range length.
+//   plan    blocks per sequence -> exclusive prefix; then for each wave the (r, h, b)
+//           at which its range starts and the range length.  Batches of up to 1024
+//           sequences need no launch for this: every attend wave derives its own
+//           range from seq_lens in registers.  Larger batches run a one-workgroup
+//           planning kernel first.
 //   attend  one 64-lane wave per range.  The wave walks its range block by block,
 //           always one block of loads ahead of the arithmetic, across sequence and
 //           head boundaries without draining.  Each maximal run of blocks of one
@@ -18,7 +21,10 @@
 //           pieces: one cut at its range start and one cut at its range end.
 //   merge   one wave per range boundary: if the boundary cuts a (r, h), combines the
 //           partials of the waves that share it exactly (rescale by exp2(m_c - m))
-//           and writes the output; also writes zeros for empty sequences.
+//           and writes the output; also writes zeros for empty sequences.  When the
+//           caller asked for the step's counter update as well (Algorithm 2 charges
+//           the counters right after forward_decode), extra workgroups of this launch
+//           do it.
 //
 // Lane mapping inside a wave: lane = 16 * row + sub.  A 16-byte load instruction
 // covers 4 tokens x 128 dims: row picks the token (4 * i + row for load i of a
@@ -26,7 +32,7 @@
 // operations per lane plus a 4-step DPP all-reduce inside the 16-lane row; the V
 // update needs no cross-lane traffic.  The 4 rows keep separate softmax states
 // that are merged once per piece.
-#include "vtc_internal.h"
+#include "counter_terms.h"
 
 namespace vtc {
 
@@ -123,6 +129,106 @@ __global__ __launch_bounds__(kPlanThreads) void decode_plan_kernel(const int32_t
     }
     wave_desc[w] = d;
   }
+}
+
+// ------------------------------------------------------------- self-plan ----
+// The same plan without a launch, for batches of at most 64 x 16 sequences: every wave computes
+// the block prefix in registers (lane i holds sequences i*c .. i*c+c-1, c = ceil(N / 64)) and looks
+// up only its own range start.  Returns (r, h, b, n_blocks); n_blocks = 0 for a wave without a range.
+// Wave 0 also writes the header that the merge kernel reads.
+constexpr int kSelfPlanPerLane = 16;
+constexpr int kSelfPlanMaxSeqs = VTC_DECODE_SELF_PLAN ? kWave * kSelfPlanPerLane : 0;
+
+__device__ __forceinline__ int4 self_plan(const int32_t* __restrict__ seq_lens, int num_seqs, int num_kv_heads,
+                                          int max_tokens, int max_waves, int wave, int lane,
+                                          DecodeHeader* __restrict__ header, int32_t* lens_lds) {
+  // Every resident wave runs this before its first load, so it is kept short: sequences are handled four
+  // at a time and groups past ceil(N / 64) are skipped by a uniform branch.
+  const int per_lane = (num_seqs + kWave - 1) / kWave;
+  const int first = lane * per_lane;
+  // seq_lens is read with coalesced loads (thousands of waves read the same few lines at the same
+  // moment) and redistributed through LDS so that each lane ends up with its own run of sequences
+#pragma unroll
+  for (int c = 0; c < kSelfPlanPerLane; c += 4) {
+    if (c < per_lane) {
+      int len[4];
+#pragma unroll
+      for (int j = 0; j < 4; ++j) len[j] = seq_lens[min((c + j) * kWave + lane, num_seqs - 1)];   // clamped: always valid
+#pragma unroll
+      for (int j = 0; j < 4; ++j) {
+        const int r = (c + j) * kWave + lane;          // < 1024 = the size of lens_lds
+        lens_lds[r] = r < num_seqs ? (min(max(len[j], 0), max_tokens) + kBlockSize - 1) / kBlockSize : 0;
+      }
+    }
+  }
+  __syncthreads();                         // one wave per workgroup: orders the LDS writes before the reads
+  int nbv[kSelfPlanPerLane];
+#pragma unroll
+  for (int j = 0; j < kSelfPlanPerLane; ++j) nbv[j] = 0;
+#pragma unroll
+  for (int c = 0; c < kSelfPlanPerLane; c += 4) {
+    if (c < per_lane) {
+#pragma unroll
+      for (int j = 0; j < 4; ++j) nbv[c + j] = c + j < per_lane ? lens_lds[first + c + j] : 0;
+    }
+  }
+  int mine = 0;
+#pragma unroll
+  for (int j = 0; j < kSelfPlanPerLane; ++j) mine += nbv[j];
+  int incl = mine;
+#pragma unroll
+  for (int off = 1; off < kWave; off <<= 1) {
+    const int y = __shfl_up(incl, off);
+    if (lane >= off) incl += y;
+  }
+  const int total_blocks = __builtin_amdgcn_readlane(incl, kWave - 1);
+  const int excl = incl - mine;                                // blocks of all sequences before this lane's
+  const long long gtot = (long long)total_blocks * num_kv_heads;
+  const long long want = (gtot + kMinBlocksPerWave - 1) / kMinBlocksPerWave;
+  const int waves = (int)(want < (long long)max_waves ? want : (long long)max_waves);
+  RangeMap map{0, 0u, 1u};
+  if (waves > 0) {
+    if (gtot <= 0xffffffffll)                                  // the usual case: 32-bit division
+      map = RangeMap{(long long)((uint32_t)gtot / (uint32_t)waves), (uint32_t)gtot % (uint32_t)waves, (uint32_t)waves};
+    else
+      map = RangeMap{gtot / waves, (uint32_t)(gtot % waves), (uint32_t)waves};
+  }
+  if (wave == 0 && lane == 0) {
+    header->gtot = gtot;
+    header->quot = map.quot;
+    header->rem = (int)map.rem;
+    header->waves = waves;
+  }
+  if (wave >= waves) return make_int4(0, 0, 0, 0);
+  const long long g = map.start(wave);
+  const long long n = map.start(wave + 1) - g;
+  // Sequence r owns the stream positions [Hkv * before_r, Hkv * (before_r + nb_r)), so g lies in the
+  // sequence whose block range [before_r, before_r + nb_r) contains floor(g / Hkv).
+  const int gq = gtot <= 0xffffffffll ? (int)((uint32_t)g / (uint32_t)num_kv_heads) : (int)(g / num_kv_heads);
+  // the prefix is non-decreasing over the lanes: the last lane that starts at or before g owns it
+  const unsigned long long below = __ballot(excl <= gq);
+  const int owner = __builtin_amdgcn_readfirstlane(__popcll(below) - 1);
+  int before = excl, found_r = 0, found_before = 0, found_nb = 1;
+#pragma unroll
+  for (int c = 0; c < kSelfPlanPerLane; c += 4) {
+    if (c < per_lane) {
+#pragma unroll
+      for (int j = 0; j < 4; ++j) {
+        const int nb = nbv[c + j];
+        if (nb > 0 && before <= gq && gq < before + nb) {
+          found_r = first + c + j;
+          found_before = before;
+          found_nb = nb;
+        }
+        before += nb;
+      }
+    }
+  }
+  const int r = __builtin_amdgcn_readlane(found_r, owner);
+  const int p0 = __builtin_amdgcn_readlane(found_before, owner);
+  const uint32_t nb = (uint32_t)__builtin_amdgcn_readlane(found_nb, owner);
+  const uint32_t off = (uint32_t)(g - (long long)p0 * num_kv_heads);       // < nb * Hkv < 2^31
+  return make_int4(r, (int)(off / nb), (int)(off % nb), (int)n);
 }
 
 // ---------------------------------------------------------------- attend ----
@@ -391,13 +497,28 @@ struct MfmaEngine {
       for (int db = 0; db < 8; ++db) acc[db] *= alpha;
     }
     const u32x2 pb = u32x2{pack2<T>(p[0], p[1]), pack2<T>(p[2], p[3])};   // P^T: tokens 4*kg + 0..3 of head j
+    // bf16 keeps 8 bits of a weight.  What the rounding dropped goes through the second product as an
+    // operand of its own, so the weights act with 16 bits (fp16's 11 bits are left as they are).
+    constexpr bool kSplitP = __is_same(T, BF16) && VTC_DECODE_BF16_SPLIT_P;
+    u32x2 pr = u32x2{0u, 0u};
+    if constexpr (kSplitP) {
+      pr = u32x2{pack2<T>(p[0] - __builtin_bit_cast(float, pb[0] << 16),
+                          p[1] - __builtin_bit_cast(float, pb[0] & 0xffff0000u)),
+                 pack2<T>(p[2] - __builtin_bit_cast(float, pb[1] << 16),
+                          p[3] - __builtin_bit_cast(float, pb[1] & 0xffff0000u))};
+    }
     // O^T[dim][head] += V^T . P^T; lane j of group kg addresses token 4*kg + j/4, dims 4*(j%4).. of each 16-dim block
     typedef __attribute__((address_space(3))) s16x4 lds_s16x4;
     const uint16_t* vrow = v_lds + (4 * kg + (j >> 2)) * kPitchV + 4 * (j & 3);
+    u32x2 vt[8];
 #pragma unroll
     for (int db = 0; db < 8; ++db) {
-      const s16x4 vt = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4*)(vrow + db * 16));
-      acc[db] = mfma_pv(__builtin_bit_cast(u32x2, vt), pb, acc[db]);
+      vt[db] = __builtin_bit_cast(u32x2, __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4*)(vrow + db * 16)));
+      acc[db] = mfma_pv(vt[db], pb, acc[db]);
+    }
+    if constexpr (kSplitP) {                 // second pass, so that no product waits for the one before it
+#pragma unroll
+      for (int db = 0; db < 8; ++db) acc[db] = mfma_pv(vt[db], pr, acc[db]);
     }
   }
 
@@ -437,15 +558,23 @@ template <typename T, int G, typename Engine>
 __global__ __launch_bounds__(kWave, Engine::kMinWavesPerSimd) void decode_attend_kernel(
     const uint16_t* __restrict__ q, const uint16_t* __restrict__ k_cache, const uint16_t* __restrict__ v_cache,
     const int32_t* __restrict__ block_table, const int32_t* __restrict__ seq_lens, uint16_t* __restrict__ out,
-    const int4* __restrict__ wave_desc, float2* __restrict__ part_ml, float* __restrict__ part_acc,
-    int32_t num_kv_heads, int32_t max_blocks_per_seq, float scale2) {
+    int4* __restrict__ wave_desc, float2* __restrict__ part_ml, float* __restrict__ part_acc,
+    int32_t num_kv_heads, int32_t max_blocks_per_seq, float scale2, int32_t self_plan_seqs,
+    DecodeHeader* __restrict__ header) {
   constexpr int kQRegs = Engine::kQRegs;
   __shared__ __attribute__((aligned(16))) uint16_t lds[Engine::kLdsElems > 0 ? Engine::kLdsElems : 8];
   const int lane = threadIdx.x;
   const int num_q_heads = num_kv_heads * G;
   const int max_tokens = max_blocks_per_seq * kBlockSize;
   const int wave = blockIdx.x;
-  const int4 desc_v = wave_desc[wave];
+  int4 desc_v;
+  if (self_plan_seqs > 0) {                // no planning launch: derive the range here, leave it for the merge
+    __shared__ int32_t lens_lds[kSelfPlanMaxSeqs > 0 ? kSelfPlanMaxSeqs : 1];
+    desc_v = self_plan(seq_lens, self_plan_seqs, num_kv_heads, max_tokens, gridDim.x, wave, lane, header, lens_lds);
+    if (lane == 0) wave_desc[wave] = desc_v;
+  } else {
+    desc_v = wave_desc[wave];
+  }
   // the descriptor is the same for all lanes: keep it (and everything derived from it) in scalar registers
   const int4 desc = make_int4(__builtin_amdgcn_readfirstlane(desc_v.x), __builtin_amdgcn_readfirstlane(desc_v.y),
                               __builtin_amdgcn_readfirstlane(desc_v.z), __builtin_amdgcn_readfirstlane(desc_v.w));
@@ -555,21 +684,34 @@ __global__ __launch_bounds__(kWave, Engine::kMinWavesPerSimd) void decode_attend
 // (r, kv head) and wave w-1 holds its beginning, the block combines the pieces of waves
 // w-1, w, w+1, ... for one of the G query heads of that kv head (blockIdx.y).  Blocks past the
 // waves zero the output rows of empty sequences.
+constexpr int kFusedCounterTable = 512;          // clients whose sums a merge-launch workgroup keeps in LDS
+constexpr int kFusedCounterRequests = 1024;      // requests per such workgroup
+
 template <typename T>
 __global__ __launch_bounds__(kWave) void decode_merge_kernel(const DecodeHeader* __restrict__ header,
-                                                             const int32_t* __restrict__ seg_prefix,
+                                                             const int32_t* __restrict__ seq_lens,
                                                              const int4* __restrict__ wave_desc,
                                                              const float2* __restrict__ part_ml,
                                                              const float* __restrict__ part_acc,
                                                              uint16_t* __restrict__ out, int32_t num_seqs,
                                                              int32_t num_q_heads, int32_t num_kv_heads,
-                                                             int32_t max_waves) {
+                                                             int32_t max_waves, int32_t max_tokens,
+                                                             CounterJob job) {
+  __shared__ u64 counter_table[kFusedCounterTable];
   const int lane = threadIdx.x;                          // dims 2*lane, 2*lane+1
   const int group = num_q_heads / num_kv_heads;
   const int g = blockIdx.y;                              // query head inside the group
+  if ((int)blockIdx.x >= max_waves + num_seqs) {         // the step's counter update
+    if (g != 0) return;
+    const int begin = ((int)blockIdx.x - max_waves - num_seqs) * kFusedCounterRequests;
+    counter_reduce_slice<kWave, kFusedCounterTable>(counter_table, job.counters, job.num_clients, job.client_ids,
+                                                    begin, min(job.n, begin + kFusedCounterRequests),
+                                                    LinearTerm{job.n_in, job.n_out, job.w_p, job.w_q});
+    return;
+  }
   if ((int)blockIdx.x >= max_waves) {                    // empty sequences: all-zero rows
     const int r = blockIdx.x - max_waves;
-    if (g != 0 || seg_prefix[r + 1] - seg_prefix[r] > 0) return;
+    if (g != 0 || min(seq_lens[r], max_tokens) > 0) return;
     uint32_t* dst = reinterpret_cast<uint32_t*>(out + (size_t)r * num_q_heads * kHeadDim);
     for (int i = lane; i < num_q_heads * (kHeadDim / 2); i += kWave) dst[i] = 0u;
     return;
@@ -580,7 +722,7 @@ __global__ __launch_bounds__(kWave) void decode_merge_kernel(const DecodeHeader*
   const int4 d = wave_desc[w];                           // (r, kv head, block) where wave w starts
   if (d.z == 0) return;                                  // the cut coincides with a sequence-head boundary
   if (d.z > wave_desc[w - 1].w) return;                  // the beginning lies before wave w-1: an earlier block merges it
-  const int nb = seg_prefix[d.x + 1] - seg_prefix[d.x];
+  const int nb = (min(max(seq_lens[d.x], 0), max_tokens) + kBlockSize - 1) / kBlockSize;
   const RangeMap map{header->quot, (uint32_t)header->rem, (uint32_t)waves};
   const long long g1 = map.start(w) + (nb - d.z);         // end of the sequence-head in the stream
   {
@@ -611,7 +753,8 @@ __global__ __launch_bounds__(kWave) void decode_merge_kernel(const DecodeHeader*
 template <typename T, int G, typename Engine>
 static int launch_typed(const vtc_attn_params& p, int32_t num_seqs, const void* q, const void* k_cache,
                         const void* v_cache, const int32_t* block_table, const int32_t* seq_lens, void* out,
-                        void* workspace, hipStream_t stream, hipEvent_t ev_begin, hipEvent_t ev_end) {
+                        void* workspace, hipStream_t stream, hipEvent_t ev_begin, hipEvent_t ev_end,
+                        const CounterJob& job) {
   const DecodeWorkspace ws = decode_workspace_layout(p, num_seqs, 0);
   char* base = static_cast<char*>(workspace);
   DecodeHeader* header = reinterpret_cast<DecodeHeader*>(base + ws.header_off);
@@ -633,17 +776,21 @@ static int launch_typed(const vtc_attn_params& p, int32_t num_seqs, const void* 
   long long resident = (long long)device_cu_count() * waves_per_cu;
   const int grid = (int)(resident < kMaxDecodeWaves ? resident : kMaxDecodeWaves);
 
-  hipLaunchKernelGGL(decode_plan_kernel, dim3(1), dim3(kPlanThreads), 0, stream, seq_lens, num_seqs, p.num_kv_heads,
-                     max_tokens, grid, header, seg_prefix, wave_desc);
+  const bool self_plan = num_seqs <= kSelfPlanMaxSeqs;
+  if (!self_plan)
+    hipLaunchKernelGGL(decode_plan_kernel, dim3(1), dim3(kPlanThreads), 0, stream, seq_lens, num_seqs,
+                       p.num_kv_heads, max_tokens, grid, header, seg_prefix, wave_desc);
   if (ev_begin && hipEventRecord(ev_begin, stream) != hipSuccess) return VTC_ERR_HIP;
   hipLaunchKernelGGL((decode_attend_kernel<T, G, Engine>), dim3(grid), dim3(kWave), 0, stream,
                      static_cast<const uint16_t*>(q), static_cast<const uint16_t*>(k_cache),
                      static_cast<const uint16_t*>(v_cache), block_table, seq_lens, static_cast<uint16_t*>(out),
-                     wave_desc, part_ml, part_acc, p.num_kv_heads, p.max_blocks_per_seq, p.scale * kLog2e);
+                     wave_desc, part_ml, part_acc, p.num_kv_heads, p.max_blocks_per_seq, p.scale * kLog2e,
+                     self_plan ? num_seqs : 0, header);
   if (ev_end && hipEventRecord(ev_end, stream) != hipSuccess) return VTC_ERR_HIP;
-  hipLaunchKernelGGL((decode_merge_kernel<T>), dim3(grid + num_seqs, G), dim3(kWave), 0, stream, header, seg_prefix,
-                     wave_desc, part_ml, part_acc, static_cast<uint16_t*>(out), num_seqs, p.num_q_heads,
-                     p.num_kv_heads, grid);
+  const int counter_blocks = (job.n + kFusedCounterRequests - 1) / kFusedCounterRequests;
+  hipLaunchKernelGGL((decode_merge_kernel<T>), dim3(grid + num_seqs + counter_blocks, G), dim3(kWave), 0, stream,
+                     header, seq_lens, wave_desc, part_ml, part_acc, static_cast<uint16_t*>(out), num_seqs,
+                     p.num_q_heads, p.num_kv_heads, grid, max_tokens, job);
   return hipGetLastError() == hipSuccess ? VTC_OK : VTC_ERR_HIP;
 }
 
@@ -658,24 +805,26 @@ using GqaEngine = ValuEngine<T, G>;
 template <typename T>
 static int launch_group(const vtc_attn_params& p, int32_t num_seqs, const void* q, const void* k_cache,
                         const void* v_cache, const int32_t* block_table, const int32_t* seq_lens, void* out,
-                        void* workspace, hipStream_t stream, hipEvent_t ev_begin, hipEvent_t ev_end) {
+                        void* workspace, hipStream_t stream, hipEvent_t ev_begin, hipEvent_t ev_end,
+                        const CounterJob& job) {
   switch (p.num_q_heads / p.num_kv_heads) {
-    case 1: return launch_typed<T, 1, ValuEngine<T, 1>>(p, num_seqs, q, k_cache, v_cache, block_table, seq_lens, out, workspace, stream, ev_begin, ev_end);
-    case 2: return launch_typed<T, 2, GqaEngine<T, 2>>(p, num_seqs, q, k_cache, v_cache, block_table, seq_lens, out, workspace, stream, ev_begin, ev_end);
-    case 4: return launch_typed<T, 4, GqaEngine<T, 4>>(p, num_seqs, q, k_cache, v_cache, block_table, seq_lens, out, workspace, stream, ev_begin, ev_end);
-    case 8: return launch_typed<T, 8, GqaEngine<T, 8>>(p, num_seqs, q, k_cache, v_cache, block_table, seq_lens, out, workspace, stream, ev_begin, ev_end);
+    case 1: return launch_typed<T, 1, ValuEngine<T, 1>>(p, num_seqs, q, k_cache, v_cache, block_table, seq_lens, out, workspace, stream, ev_begin, ev_end, job);
+    case 2: return launch_typed<T, 2, GqaEngine<T, 2>>(p, num_seqs, q, k_cache, v_cache, block_table, seq_lens, out, workspace, stream, ev_begin, ev_end, job);
+    case 4: return launch_typed<T, 4, GqaEngine<T, 4>>(p, num_seqs, q, k_cache, v_cache, block_table, seq_lens, out, workspace, stream, ev_begin, ev_end, job);
+    case 8: return launch_typed<T, 8, GqaEngine<T, 8>>(p, num_seqs, q, k_cache, v_cache, block_table, seq_lens, out, workspace, stream, ev_begin, ev_end, job);
     default: return VTC_ERR_UNSUPPORTED;
   }
 }
 
 int launch_decode(const vtc_attn_params& p, int32_t num_seqs, const void* q, const void* k_cache,
                   const void* v_cache, const int32_t* block_table, const int32_t* seq_lens, void* out,
-                  void* workspace, hipStream_t stream, hipEvent_t ev_begin, hipEvent_t ev_end) {
+                  void* workspace, hipStream_t stream, hipEvent_t ev_begin, hipEvent_t ev_end,
+                  const CounterJob& job) {
   // the flattened block index must fit the 64-bit products used above and the grid limits of the merge launch
   if ((long long)num_seqs * p.max_blocks_per_seq >= (1ll << 31)) return VTC_ERR_UNSUPPORTED;
   if (p.dtype == VTC_F16)
-    return launch_group<F16>(p, num_seqs, q, k_cache, v_cache, block_table, seq_lens, out, workspace, stream, ev_begin, ev_end);
-  return launch_group<BF16>(p, num_seqs, q, k_cache, v_cache, block_table, seq_lens, out, workspace, stream, ev_begin, ev_end);
+    return launch_group<F16>(p, num_seqs, q, k_cache, v_cache, block_table, seq_lens, out, workspace, stream, ev_begin, ev_end, job);
+  return launch_group<BF16>(p, num_seqs, q, k_cache, v_cache, block_table, seq_lens, out, workspace, stream, ev_begin, ev_end, job);
 }
 
 }  // namespace vtc

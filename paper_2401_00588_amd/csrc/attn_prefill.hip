@@ -204,6 +204,7 @@ __global__ __launch_bounds__(kPfThreads, 2) void prefill_chunk_kernel(
       // ---- P^T = exp2(scaled logit - m), packed to the storage type as the B operands
       float psum = 0.f;
       u32x4 pb[2][2];
+      constexpr uint32_t kOnes = __is_same(T, F16) ? 0x3c003c00u : 0x3f803f80u;   // (1, 1) in the storage type
 #pragma unroll
       for (int sb = 0; sb < 2; ++sb)
 #pragma unroll
@@ -212,8 +213,10 @@ __global__ __launch_bounds__(kPfThreads, 2) void prefill_chunk_kernel(
           for (int w = 0; w < 4; ++w) {
             const float pa = fast_exp2(fmaf(sacc[sb][8 * t + 2 * w], scale2, -m_sub));
             const float pc = fast_exp2(fmaf(sacc[sb][8 * t + 2 * w + 1], scale2, -m_sub));
-            psum += pa + pc;
             pb[sb][t][w] = pack2<T>(pa, pc);
+            // the row sum adds up the weights as the second product will see them (after rounding to the
+            // storage type), so the output stays an exact convex combination of the V rows
+            psum = dot2<T>(pb[sb][t][w], kOnes, psum);
           }
       l_run = l_run * alpha + psum;
       if (__builtin_amdgcn_ballot_w64(alpha != 1.f) != 0ull) {      // skip the rescale when no row's maximum moved

@@ -14,7 +14,7 @@
 // the result is the same for every execution order.  Client tables larger than
 // the LDS table fall back to global atomics per request.  Arithmetic is done on
 // unsigned 64-bit values, i.e. exact two's-complement wrap-around.
-#include "vtc_internal.h"
+#include "counter_terms.h"
 
 namespace vtc {
 
@@ -22,85 +22,15 @@ constexpr int kCounterThreads = 256;
 constexpr int kLdsClients = 4096;              // 32 KiB of int64
 constexpr int kRequestsPerWorkgroup = 4096;
 
-using u64 = unsigned long long;
-
-// ---- per-request terms -------------------------------------------------------
-struct LinearTerm {                            // w_p * n_p + w_q * n_q
-  const int32_t* __restrict__ n_in;
-  const int32_t* __restrict__ n_out;
-  u64 w_p, w_q;
-  __device__ __forceinline__ u64 operator()(int r, int) const {
-    const long long np = n_in ? (long long)n_in[r] : 0ll;
-    const long long nq = n_out ? (long long)n_out[r] : 0ll;
-    return w_p * (u64)np + w_q * (u64)nq;
-  }
-};
-
-struct CostTerm {                              // (h(new) - h(old)) * multiplier[client]
-  const int32_t* __restrict__ p_old;
-  const int32_t* __restrict__ q_old;
-  const int32_t* __restrict__ p_new;
-  const int32_t* __restrict__ q_new;
-  const int64_t* __restrict__ multiplier;      // may be null
-  u64 c0, cp, cq, cpp, cpq, cqq;
-  __device__ __forceinline__ u64 h(long long np, long long nq) const {
-    const u64 p = (u64)np, q = (u64)nq;
-    return c0 + cp * p + cq * q + cpp * p * p + cpq * p * q + cqq * q * q;
-  }
-  __device__ __forceinline__ u64 operator()(int r, int client) const {
-    const long long po = p_old[r], qo = q_old[r];
-    // a request none of whose tokens has been processed has cost 0, not h(0, 0)
-    const u64 old_cost = (po == 0 && qo == 0) ? 0ull : h(po, qo);
-    u64 delta = h(p_new[r], q_new[r]) - old_cost;
-    if (multiplier) delta *= (u64)multiplier[client];
-    return delta;
-  }
-};
-
-struct PredictedTerm {                         // Algorithm 3, "adjust the cost of output tokens"
-  const int32_t* __restrict__ n_output;
-  const int32_t* __restrict__ n_predicted;
-  const int32_t* __restrict__ finished;
-  u64 w_q;
-  __device__ __forceinline__ u64 operator()(int r, int) const {
-    const long long delta = (long long)n_output[r] - (long long)n_predicted[r];
-    u64 add = 0ull;
-    if (delta > 0) add += w_q;                                   // prediction used up: pay per token
-    if (finished[r] != 0 && delta < 0) add += w_q * (u64)delta;  // refund the unused pre-payment
-    return add;
-  }
-};
-
 template <typename Term>
 __global__ __launch_bounds__(kCounterThreads) void counter_reduce_kernel(u64* __restrict__ counters,
                                                                          int32_t num_clients,
                                                                          const int32_t* __restrict__ client_ids,
                                                                          int32_t n, Term term) {
   __shared__ u64 table[kLdsClients];
-  const bool use_lds = num_clients <= kLdsClients;
-  if (use_lds) {
-    for (int i = threadIdx.x; i < num_clients; i += kCounterThreads) table[i] = 0ull;
-    __syncthreads();
-  }
   const int begin = blockIdx.x * kRequestsPerWorkgroup;
-  const int end = min(n, begin + kRequestsPerWorkgroup);
-  for (int r = begin + (int)threadIdx.x; r < end; r += kCounterThreads) {
-    const int32_t c = client_ids[r];
-    if (c < 0 || c >= num_clients) continue;
-    const u64 delta = term(r, c);
-    if (delta == 0ull) continue;
-    if (use_lds)
-      atomicAdd(&table[c], delta);
-    else
-      atomicAdd(&counters[c], delta);
-  }
-  if (use_lds) {
-    __syncthreads();
-    for (int i = threadIdx.x; i < num_clients; i += kCounterThreads) {
-      const u64 d = table[i];
-      if (d != 0ull) atomicAdd(&counters[i], d);
-    }
-  }
+  counter_reduce_slice<kCounterThreads, kLdsClients>(table, counters, num_clients, client_ids, begin,
+                                                     min(n, begin + kRequestsPerWorkgroup), term);
 }
 
 template <typename Term>

@@ -31,6 +31,12 @@ constexpr float kLog2e = 1.4426950408889634f;
 #ifndef VTC_DECODE_MIN_BLOCKS_PER_WAVE
 #define VTC_DECODE_MIN_BLOCKS_PER_WAVE 2 // small batches use fewer waves rather than shorter ranges
 #endif
+#ifndef VTC_DECODE_BF16_SPLIT_P
+#define VTC_DECODE_BF16_SPLIT_P 1        // 1: the matrix-core engine feeds bf16 weights as two operands (16 bits)
+#endif
+#ifndef VTC_DECODE_SELF_PLAN
+#define VTC_DECODE_SELF_PLAN 1           // 1: batches of <= 1024 sequences skip the planning launch
+#endif
 
 // Decode attention cuts the batch's stream of KV blocks into one range per wave.
 constexpr int kMaxDecodeWaves = 8192;                          // upper bound on the launch, sizes the workspace
@@ -39,7 +45,7 @@ constexpr int kMinBlocksPerWave = VTC_DECODE_MIN_BLOCKS_PER_WAVE;
 // One fp32 partial result of a piece: running max m (log2 domain), sum l, acc[128].
 constexpr int kPartialFloats = kHeadDim;
 
-// Written by the planning kernel, read by the merge kernel.
+// Written by the planning kernel (or by wave 0 of a self-planning launch), read by the merge kernel.
 struct DecodeHeader {
   long long gtot;   // KV blocks in the stream: (sum over sequences of blocks) * num_kv_heads
   long long quot;   // gtot / waves
@@ -167,10 +173,23 @@ inline int check_params(const vtc_attn_params* p) {
 
 int device_cu_count();   // compute units of the current device (cached per device)
 
+// A counter update that rides in the last launch of a decode step (Algorithm 2 charges the
+// counters right after forward_decode).  n == 0: none.
+struct CounterJob {
+  unsigned long long* counters;
+  int32_t num_clients;
+  const int32_t* client_ids;
+  const int32_t* n_in;
+  const int32_t* n_out;
+  int32_t n;
+  unsigned long long w_p, w_q;
+};
+
 // Kernel launchers (one translation unit each).
 int launch_decode(const vtc_attn_params& p, int32_t num_seqs, const void* q, const void* k_cache,
                   const void* v_cache, const int32_t* block_table, const int32_t* seq_lens, void* out,
-                  void* workspace, hipStream_t stream, hipEvent_t ev_begin, hipEvent_t ev_end);
+                  void* workspace, hipStream_t stream, hipEvent_t ev_begin, hipEvent_t ev_end,
+                  const CounterJob& counter_job);
 int launch_prefill(const vtc_attn_params& p, int32_t num_seqs, const void* q, const int32_t* cu_q_lens,
                    int32_t max_q_len, const void* k_cache, const void* v_cache, const int32_t* block_table,
                    const int32_t* seq_lens, void* out, hipStream_t stream);

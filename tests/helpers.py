@@ -46,3 +46,27 @@ def bits_to_f64_via_torch(bits: np.ndarray, dtype: str) -> np.ndarray:
     t = torch.from_numpy(bits.view(np.int16).copy())
     t = t.view(torch.float16 if dtype == "f16" else torch.bfloat16)
     return t.to(torch.float64).numpy()
+
+
+# ---- the floating-point bar of the GPU parity tests ---------------------------------------------------
+TOL = {"f16": 2e-3, "bf16": 1e-2}          # max-abs against the unrounded fp64 oracle
+_MANTISSA_BITS = {"f16": 10, "bf16": 7}
+
+
+def elementwise_tolerance(want: np.ndarray, dtype: str) -> np.ndarray:
+    """The bound every output element is held to.
+
+    It is the flat max-abs tolerance wherever the output format can express a result that close.  From
+    |o| >= 4 on it cannot: there the spacing of bf16 is 2^-5 (of fp16 2^-8), so even the correctly
+    rounded exact result may be off by half of that, 1.56e-2 (1.95e-3).  Such elements -- a handful per
+    million with N(0,1) values and very few keys -- are held to half a unit in the last place of the
+    output format plus a fifth of the flat tolerance for the arithmetic before the final rounding.
+    """
+    a = np.maximum(np.abs(np.asarray(want, dtype=np.float64)), 2.0 ** -24)
+    half_ulp = 0.5 * np.exp2(np.floor(np.log2(a)) - _MANTISSA_BITS[dtype])
+    return np.maximum(TOL[dtype], half_ulp + 0.2 * TOL[dtype])
+
+
+def within_tolerance(got: np.ndarray, want: np.ndarray, dtype: str) -> bool:
+    got = np.asarray(got, dtype=np.float64)
+    return bool(np.isfinite(got).all() and (np.abs(got - want) <= elementwise_tolerance(want, dtype)).all())

@@ -30,7 +30,8 @@ def test_every_declared_symbol_is_exported(lib):
     names = _declared_symbols()
     assert {"vtc_attn_decode", "vtc_attn_decode_profiled", "vtc_attn_prefill_chunk", "vtc_counter_update",
             "vtc_counter_update_cost", "vtc_counter_update_predicted", "vtc_kv_append", "vtc_attn_workspace_bytes",
-            "vtc_debug_gather_slots", "vtc_strerror", "vtc_version"} <= set(names)
+            "vtc_debug_gather_slots", "vtc_strerror", "vtc_version", "vtc_step_decode",
+            "vtc_step_decode_profiled"} <= set(names)
     for name in names:
         assert getattr(lib, name) is not None
 
@@ -78,6 +79,8 @@ def test_bad_params_are_rejected_by_every_attention_entry_point(lib, kw, code):
     assert lib.vtc_attn_decode(ctypes.byref(p), 1, one, one, one, one, one, one, one, 1 << 30, None) == code
     assert lib.vtc_attn_prefill_chunk(ctypes.byref(p), 1, one, one, 1, one, one, one, one, one, None, 0, None) == code
     assert lib.vtc_debug_gather_slots(ctypes.byref(p), 1, one, one, one, 1, one, None) == code
+    assert lib.vtc_step_decode(ctypes.byref(p), 1, one, one, one, one, one, one, one, 2, one, one, one, 1, 1, 2, one,
+                               1 << 30, None) == code
 
 
 def test_null_pointers_sizes_alignment_and_workspace(lib):
@@ -148,3 +151,32 @@ def test_missing_library_is_a_loud_error(monkeypatch):
     monkeypatch.setattr(binding, "_LIB_NAME", "libvtc_not_built.so")
     with pytest.raises(RuntimeError, match="no CPU fallback"):
         binding.load_library()
+
+
+def test_fused_step_validates_both_halves_before_enqueueing(lib):
+    p = good_params()
+    a = ctypes.c_void_p(4096)
+    need = vtc.vtc_attn_workspace_bytes(p, 4, 0)
+
+    def call(num_seqs=4, attn=None, counters=a, num_clients=3, ids=a, n_in=a, n_out=a, n=4, ws=a, ws_bytes=need):
+        attn = [a] * 6 if attn is None else attn
+        return lib.vtc_step_decode(ctypes.byref(p), num_seqs, *attn, counters, num_clients, ids, n_in, n_out, n, 1, 2,
+                                   ws, ws_bytes, None)
+
+    assert call(num_seqs=-1) == -1
+    assert call(n=-1) == -1
+    assert call(num_clients=-1) == -1
+    assert call(counters=None) == -1                       # a charge was asked for: its arrays must be there
+    assert call(ids=None) == -1
+    for hole in range(6):                                  # the attention half's pointers
+        attn = [a] * 6
+        attn[hole] = None
+        assert call(attn=attn) == -1
+    assert call(ws=None) == -1
+    assert call(ws_bytes=need - 1) == -3
+    assert call(ws=ctypes.c_void_p(4096 + 64)) == -1
+    # nothing to do at all is a successful no-op, whatever the pointers are
+    assert lib.vtc_step_decode(ctypes.byref(p), 0, None, None, None, None, None, None, None, 3, None, None, None, 0,
+                               1, 2, None, 0, None) == 0
+    assert lib.vtc_step_decode(ctypes.byref(p), 0, None, None, None, None, None, None, None, 0, a, a, a, 5,
+                               1, 2, None, 0, None) == 0   # no clients: every id is out of range

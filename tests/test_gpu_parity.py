@@ -1,7 +1,9 @@
 """Parity of the HIP path with the CPU oracle, through the C ABI (needs an MI355X).
 
 Tolerances (max-abs against the *unrounded* fp64 oracle): 2e-3 for fp16, 1e-2 for
-bf16.  Counters and slot indices are compared bit for bit.
+bf16, held elementwise (tests/helpers.py: from |o| >= 4 on the output format itself
+cannot meet them and the bound follows its spacing).  Counters and slot indices
+are compared bit for bit.
 """
 import math
 import sys
@@ -13,12 +15,12 @@ import paper_2401_00588_amd as vtc
 from oracle import attention as OA
 from oracle.counters import counter_update as oracle_counter_update
 from oracle.counters import gather_slots as oracle_gather_slots
+from tests.helpers import TOL, within_tolerance
 from workloads import (NAN_BITS, bits_to_tensor, make_block_table, make_device_step, make_qkv_numpy,
                        make_step_batch, poison_unused_rows, sequence_rows_to_host, tensor_to_bits)
 
 pytestmark = pytest.mark.gpu
 
-TOL = {"f16": 2e-3, "bf16": 1e-2}
 SCALE = 1.0 / math.sqrt(128.0)
 
 
@@ -124,7 +126,7 @@ def test_decode_ragged_lengths_match_the_oracle(torch, dtype, hq, hkv):
     got, want = _decode_case(torch, RAGGED, hq, hkv, dtype, seed=31)
     err = np.abs(got - want).max()
     say(f"  max abs err {err:.3e}  max |o| {np.abs(want).max():.3f}")
-    assert np.isfinite(got).all() and err <= TOL[dtype]
+    assert within_tolerance(got, want, dtype)
 
 
 @pytest.mark.parametrize("dtype,hq,hkv", [("f16", 32, 32), ("bf16", 32, 8)])
@@ -132,8 +134,7 @@ def test_decode_ignores_rows_past_seq_len_and_handles_empty_sequences(torch, dty
     say(f"decode poisoned tails dtype={dtype}")
     seq = [0, 1, 7, 16, 0, 250, 257, 17]
     got, want = _decode_case(torch, seq, hq, hkv, dtype, seed=32, poison=True, min_row_len=40)
-    assert np.isfinite(got).all()
-    assert np.abs(got - want).max() <= TOL[dtype]
+    assert within_tolerance(got, want, dtype)
     assert (got[0] == 0).all() and (got[4] == 0).all()
 
 
@@ -148,7 +149,24 @@ def test_decode_many_short_sequences(torch, n, hq, hkv, dtype):
     got, want = _decode_case(torch, seq, hq, hkv, dtype, seed=n + 1)
     err = np.abs(got - want).max()
     say(f"  max abs err {err:.3e}")
-    assert np.isfinite(got).all() and err <= TOL[dtype]
+    assert within_tolerance(got, want, dtype)
+    assert (got[seq == 0] == 0).all()
+
+
+@pytest.mark.parametrize("n", [1, 63, 64, 65, 130, 1000, 1024, 1025])
+def test_decode_batch_sizes_around_the_in_kernel_planning_limits(torch, n):
+    # up to 1024 sequences every wave finds its own range (16 sequences per lane at most); one more
+    # sequence and the planning kernel runs instead.  Lanes with no sequence, lanes whose sequences are
+    # all empty, and the last partly filled lane are all present in these sizes.
+    say(f"decode batch of {n} sequences")
+    rng = np.random.default_rng(7000 + n)
+    seq = rng.integers(0, 40, size=n).astype(np.int32)
+    seq[rng.integers(0, n, size=max(1, n // 8))] = 0
+    seq[rng.integers(0, n, size=2)] = 530
+    got, want = _decode_case(torch, seq, 8, 2, "f16", seed=7100 + n)
+    err = np.abs(got - want).max()
+    say(f"  max abs err {err:.3e}")
+    assert within_tolerance(got, want, "f16")
     assert (got[seq == 0] == 0).all()
 
 
@@ -184,7 +202,7 @@ def test_decode_small_configs_elementwise(torch, cfg):
                            st.block_table.cpu().numpy(), b.seq_lens, SCALE, sh.dtype)
     err = np.abs(got - want).max()
     say(f"  max abs err {err:.3e}")
-    assert err <= TOL[sh.dtype]
+    assert within_tolerance(got, want, sh.dtype)
 
 
 def _sampled_decode_check(torch, st, out, n_samples, seed):
@@ -260,7 +278,7 @@ def test_prefill_chunk_ragged_matches_the_oracle(torch, dtype, hq, hkv):
     got, want = _prefill_case(torch, PF_Q, PF_S, hq, hkv, dtype, seed=41, poison=True)
     err = np.abs(got - want)
     say(f"  max abs err {err.max():.3e}  max |o| {np.abs(want).max():.3f}")
-    assert np.isfinite(got).all() and err.max() <= TOL[dtype]
+    assert within_tolerance(got, want, dtype)
 
 
 @pytest.mark.parametrize("chunk", [0, 1])

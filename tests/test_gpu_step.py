@@ -1,0 +1,153 @@
+"""The fused decode step (attention + counter charge in one call) against the CPU oracle, through the
+C ABI (needs an MI355X).  Attention within the floating-point tolerance, counters bit-exact."""
+import math
+import sys
+
+import numpy as np
+import pytest
+
+import paper_2401_00588_amd as vtc
+from oracle import attention as OA
+from oracle.counters import counter_update
+from tests.helpers import TOL, within_tolerance
+from workloads import (bits_to_tensor, make_block_table, make_device_step, make_qkv_numpy, make_step_batch,
+                       sequence_rows_to_host, tensor_to_bits)
+
+pytestmark = pytest.mark.gpu
+SCALE = 1.0 / math.sqrt(128.0)
+
+
+def say(msg):
+    print(msg, flush=True)
+    sys.stdout.flush()
+
+
+@pytest.fixture(scope="module")
+def torch():
+    import torch as t
+
+    assert t.cuda.is_available(), "these tests need a GPU"
+    vtc.load_library()
+    return t
+
+
+def _i32(torch, a):
+    return torch.from_numpy(np.ascontiguousarray(a, dtype=np.int32)).cuda()
+
+
+def _i64(torch, a):
+    return torch.from_numpy(np.ascontiguousarray(a, dtype=np.int64)).cuda()
+
+
+def _case(torch, seq, hq, hkv, dtype, seed, clients, n_requests, with_inputs=True):
+    rng = np.random.default_rng(seed)
+    table, nb = make_block_table(rng, seq, 16)
+    q, k, v = make_qkv_numpy(rng, len(seq), hq, hkv, 128, nb, 16, dtype)
+    ids = rng.integers(-1, clients + 1, size=n_requests).astype(np.int32)      # a few ids out of range
+    n_in = rng.integers(0, 2049, size=n_requests).astype(np.int32) if with_inputs else None
+    n_out = rng.integers(0, 2, size=n_requests).astype(np.int32)
+    before = rng.integers(-10 ** 12, 10 ** 12, size=clients).astype(np.int64)
+    counters = _i64(torch, before)
+    p = vtc.make_params(hq, hkv, 128, 16, table.shape[1], dtype, SCALE)
+    out = vtc.vtc_step_decode(p, bits_to_tensor(q, dtype), bits_to_tensor(k, dtype), bits_to_tensor(v, dtype),
+                              _i32(torch, table), _i32(torch, seq), counters, _i32(torch, ids),
+                              None if n_in is None else _i32(torch, n_in), _i32(torch, n_out), 1, 2)
+    torch.cuda.synchronize()
+    got = OA.widen(tensor_to_bits(out), dtype)
+    want = OA.paged_decode(q, k, v, table, seq, SCALE, dtype)
+    want_c = counter_update(before.tolist(), ids.tolist(), None if n_in is None else n_in.tolist(), n_out.tolist(), 1, 2)
+    return got, want, counters.cpu().tolist(), want_c
+
+
+@pytest.mark.parametrize("dtype,hq,hkv,clients,extra", [("f16", 32, 32, 2, 0), ("bf16", 32, 8, 27, 16),
+                                                        ("f16", 8, 4, 700, 3000)])
+def test_step_decode_matches_the_oracle(torch, dtype, hq, hkv, clients, extra):
+    # extra > 0: the charge covers more requests than the attention (a mixed step); 700 clients do not fit
+    # the on-chip table of the fused charge, which then adds to the counters request by request
+    say(f"step_decode dtype={dtype} Hq={hq} Hkv={hkv} clients={clients} extra requests={extra}")
+    seq = [1, 2, 16, 17, 100, 255, 256, 257, 513, 700, 0, 33]
+    got, want, c_got, c_want = _case(torch, seq, hq, hkv, dtype, 910 + clients, clients, len(seq) + extra)
+    err = np.abs(got - want).max()
+    say(f"  max abs err {err:.3e}")
+    assert within_tolerance(got, want, dtype)
+    assert c_got == c_want
+
+
+@pytest.mark.parametrize("n", [1500, 1024])
+def test_step_decode_large_batches_both_planning_paths(torch, n):
+    say(f"step_decode {n} sequences")
+    rng = np.random.default_rng(n)
+    seq = rng.integers(0, 30, size=n).astype(np.int32)
+    seq[rng.integers(0, n, size=3)] = 400
+    got, want, c_got, c_want = _case(torch, seq, 4, 2, "bf16", 920 + n, 40, n, with_inputs=False)
+    say(f"  max abs err {np.abs(got - want).max():.3e}  max |o| {np.abs(want).max():.3f}")
+    assert within_tolerance(got, want, "bf16")
+    assert c_got == c_want
+
+
+def test_step_decode_halves_alone(torch):
+    say("step_decode: charge alone, attention alone")
+    rng = np.random.default_rng(930)
+    ids = rng.integers(0, 5, size=300).astype(np.int32)
+    n_out = np.ones(300, dtype=np.int32)
+    counters = _i64(torch, np.zeros(5, dtype=np.int64))
+    p = vtc.make_params(4, 4, 128, 16, 4, "f16", SCALE)
+    empty = torch.empty((0, 4, 128), dtype=torch.float16, device="cuda")
+    cache = torch.zeros((1, 4, 16, 128), dtype=torch.float16, device="cuda")
+    vtc.vtc_step_decode(p, empty, cache, cache, torch.empty((0, 4), dtype=torch.int32, device="cuda"),
+                        torch.empty((0,), dtype=torch.int32, device="cuda"), counters, _i32(torch, ids), None,
+                        _i32(torch, n_out), 1, 2)
+    torch.cuda.synchronize()
+    assert counters.cpu().tolist() == counter_update([0] * 5, ids.tolist(), None, n_out.tolist(), 1, 2)
+    # no requests to charge: the counters stay as they are, the attention still runs
+    seq = [5, 40]
+    table, nb = make_block_table(rng, seq, 16)
+    q, k, v = make_qkv_numpy(rng, 2, 4, 4, 128, nb, 16, "f16")
+    p = vtc.make_params(4, 4, 128, 16, table.shape[1], "f16", SCALE)
+    before = counters.clone()
+    out = vtc.vtc_step_decode(p, bits_to_tensor(q, "f16"), bits_to_tensor(k, "f16"), bits_to_tensor(v, "f16"),
+                              _i32(torch, table), _i32(torch, seq), counters,
+                              torch.empty((0,), dtype=torch.int32, device="cuda"), None, None, 1, 2)
+    torch.cuda.synchronize()
+    assert torch.equal(before, counters)
+    want = OA.paged_decode(q, k, v, table, seq, SCALE, "f16")
+    assert within_tolerance(OA.widen(tensor_to_bits(out), "f16"), want, "f16")
+
+
+@pytest.mark.parametrize("cfg", [3, 5])
+def test_step_decode_on_the_config_batches(torch, cfg):
+    # the launch configuration the benchmark times: counters bit-exact against the oracle, attention on
+    # sampled rows against the oracle; repeated steps keep accumulating exactly
+    say(f"step_decode on cfg{cfg}")
+    b = make_step_batch(cfg)
+    st = make_device_step(b)
+    sh = b.shape
+    p = vtc.make_params(sh.num_q_heads, sh.num_kv_heads, 128, 16, st.max_blocks_per_seq, sh.dtype, SCALE)
+    ws = torch.empty(vtc.vtc_attn_workspace_bytes(p, b.num_decode, 0), dtype=torch.uint8, device="cuda")
+    out = torch.empty_like(st.q)
+    for _ in range(3):
+        vtc.vtc_step_decode(p, st.q, st.k_cache, st.v_cache, st.block_table, st.seq_lens, st.counters,
+                            st.cu_client_ids, st.cu_n_in, st.cu_n_out, b.w_p, b.w_q, out=out, workspace=ws)
+    torch.cuda.synchronize()
+    ids, n_in, n_out = b.counter_update_args()
+    want_c = list(b.counters_before)
+    for _ in range(3):
+        want_c = counter_update(want_c, ids, n_in, n_out, b.w_p, b.w_q)
+    assert st.counters.cpu().tolist() == want_c
+    rng = np.random.default_rng(940 + cfg)
+    order = np.argsort(b.seq_lens)
+    picks = [int(order[0]), int(order[-1])] + [int(x) for x in rng.choice(b.num_decode, size=6, replace=False)]
+    group = sh.num_q_heads // sh.num_kv_heads
+    got = OA.widen(tensor_to_bits(out), sh.dtype)
+    assert np.isfinite(got).all()
+    q_bits = tensor_to_bits(st.q)
+    worst = 0.0
+    for r in picks:
+        h = int(rng.integers(0, sh.num_q_heads))
+        s_len = int(b.seq_lens[r])
+        keys = OA.widen(sequence_rows_to_host(st.k_cache, st.block_table[r], s_len, h // group), sh.dtype)
+        vals = OA.widen(sequence_rows_to_host(st.v_cache, st.block_table[r], s_len, h // group), sh.dtype)
+        want = OA.attend_one(OA.widen(q_bits[r, h], sh.dtype), keys, vals, SCALE)
+        worst = max(worst, float(np.abs(got[r, h] - want).max()))
+    say(f"  worst sampled err {worst:.3e}")
+    assert worst <= TOL[sh.dtype]

@@ -81,3 +81,21 @@ def test_snapshot_is_self_consistent(cfg):
     assert counter_update(b.counters_before, ids, n_in, n_out, b.w_p, b.w_q) == b.counters_after.tolist()
     # VTC keeps the overloaded clients' counters close together
     assert b.counters_before.max() - b.counters_before.min() < 2 * p["w_q"] * p["M"]
+
+
+def test_elementwise_tolerance_is_flat_where_the_output_format_allows_it():
+    from tests.helpers import TOL, elementwise_tolerance, within_tolerance
+
+    want = np.array([0.0, 1e-9, 0.5, 1.99, 2.0, 3.999, 4.0, 7.9, 8.0])
+    bf = elementwise_tolerance(want, "bf16")
+    assert (bf[:6] == TOL["bf16"]).all()                       # below 4 the flat 1e-2 holds
+    assert bf[6] == bf[7] == 2.0 ** -6 + 2e-3                  # [4, 8): half the spacing 2^-5, plus a fifth of the flat bar
+    assert bf[8] == 2.0 ** -5 + 2e-3
+    f = elementwise_tolerance(want, "f16")
+    assert (f[:6] == TOL["f16"]).all() and f[6] == 2.0 ** -9 + 4e-4
+    # a correctly rounded bf16 result always passes; one more unit in the last place does not
+    exact = np.array([4.0 + 2.0 ** -6 - 1e-6, 3.0 + 2.0 ** -7 - 1e-6])
+    rounded = np.array([4.0, 3.0])
+    assert within_tolerance(rounded, exact, "bf16")
+    assert not within_tolerance(rounded - np.array([2.0 ** -5, 2.0 ** -6]), exact, "bf16")
+    assert not within_tolerance(np.array([np.nan]), np.array([0.0]), "bf16")
