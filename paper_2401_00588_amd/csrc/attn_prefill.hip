@@ -7,8 +7,15 @@
 // KV head, so with grouped-query attention the 4 waves take up to 4 query heads of
 // the group for the same 32 tokens (HW = heads per workgroup), and with HW < 4 the
 // remaining waves take further 32-token tiles.  The workgroup walks the keys it can
-// see in tiles of 64 and stages each K and V tile in LDS once for all 4 waves,
-// double-buffered: the global loads of tile j+1 are in flight while tile j is used.
+// see in tiles of 64 keys.  A K and a V tile live in LDS once for all 4 waves, double-
+// buffered, and get there without passing through registers: wave w copies KV block
+// k0/16 + w of the tile with 16-byte global-to-LDS loads (a load instruction fills
+// 1 KiB = 4 rows of LDS contiguously, lane l at byte 16 l), the loads of tile j+1 being
+// in flight while tile j is used.  Rows are 256 bytes with no padding; instead the
+// 16-byte chunks of a row are permuted on the way in (the lane picks which chunk of the
+// global row it fetches): K chunk c of row r sits at position c ^ (r & 15), V chunk c at
+// c ^ 4 (r & 3), which makes the 16-byte row reads of K and the 8-byte transposing reads
+// of V hit every LDS bank equally.
 //
 // Per tile and wave, with v_mfma_f32_32x32x16 (A: 32 rows x 16, B: 16 x 32 columns):
 //   S^T = K . Q^T      2 key blocks x 8 steps over head_dim; A = 32 keys of the K tile
@@ -35,11 +42,9 @@ constexpr int kXcds = 8;                 // accelerator complex dies of an MI355
 constexpr int kPfThreads = 256;
 constexpr int kPfRows = 32;              // query rows per wave
 constexpr int kPfKTile = 64;             // keys per LDS tile
-constexpr int kPitchK = kHeadDim + 8;    // 272 B rows: 16-byte reads of 16 consecutive rows hit all banks once
-constexpr int kPitchV = kHeadDim + 32;   // 320 B rows: the 8-row x 64-byte transposing reads spread over all banks
-constexpr int kTileK = kPfKTile * kPitchK;
-static_assert(4 * kPfRows * kPitchK <= 2 * kPfKTile * kPitchK, "the four output patches must fit the K buffers");
-constexpr int kTileV = kPfKTile * kPitchV;
+constexpr int kTileElems64 = kPfKTile * kHeadDim;    // one K or V tile in LDS, unpadded (16 KiB)
+constexpr int kPitchO = kHeadDim + 8;                // output patch rows: 272 B
+static_assert(4 * kPfRows * kPitchO <= 4 * kTileElems64, "the four output patches must fit the tile buffers");
 
 template <typename T>
 __device__ __forceinline__ f32x16 mfma32(u32x4 a, u32x4 b, f32x16 c);
@@ -60,6 +65,24 @@ __device__ __forceinline__ u32x2 lds_read_tr16(const uint16_t* p) {
   return __builtin_bit_cast(u32x2, v);
 }
 
+// 16 bytes per lane from global memory straight into LDS: lane l of the wave writes LDS bytes
+// [dst + 16 l, dst + 16 l + 16); dst is wave-uniform (it travels in M0).  Issued as inline assembly so that
+// the compiler does not order every later LDS read behind it: completion is waited for explicitly
+// (s_waitcnt vmcnt(0) + barrier) before the buffer is read.  Loads the compiler does not know about can
+// only make its own vmcnt waits longer, never shorter (the counter retires in issue order).
+__device__ __forceinline__ void lds_dma16(const uint16_t* src, uint16_t* dst_uniform) {
+  typedef __attribute__((address_space(3))) uint16_t lds_u16;
+  const uint32_t lds_addr = __builtin_amdgcn_readfirstlane((uint32_t)(uintptr_t)(lds_u16*)dst_uniform);
+  asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, off" ::"s"(lds_addr), "v"(src) : "memory", "m0");
+}
+
+// The 4-byte form: lane l writes LDS bytes [dst + 4 l, dst + 4 l + 4).
+__device__ __forceinline__ void lds_dma4(const uint16_t* src, uint16_t* dst_uniform) {
+  typedef __attribute__((address_space(3))) uint16_t lds_u16;
+  const uint32_t lds_addr = __builtin_amdgcn_readfirstlane((uint32_t)(uintptr_t)(lds_u16*)dst_uniform);
+  asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dword %1, off" ::"s"(lds_addr), "v"(src) : "memory", "m0");
+}
+
 template <typename T, int HW, bool kPosScale>
 __global__ __launch_bounds__(kPfThreads, 2) void prefill_chunk_kernel(
     const uint16_t* __restrict__ q, const int32_t* __restrict__ cu_q_lens, const uint16_t* __restrict__ k_cache,
@@ -68,8 +91,10 @@ __global__ __launch_bounds__(kPfThreads, 2) void prefill_chunk_kernel(
     int32_t max_blocks_per_seq, float scale2) {
   constexpr int TT = 4 / HW;                       // 32-token tiles per workgroup
   constexpr int kTokensPerWg = kPfRows * TT;
-  __shared__ __attribute__((aligned(16))) uint16_t k_lds[2][kTileK];
-  __shared__ __attribute__((aligned(16))) uint16_t v_lds[2][kTileV];
+  __shared__ __attribute__((aligned(1024))) uint16_t lds[4 * kTileElems64];    // K buffers 0, 1, then V buffers 0, 1
+  __shared__ __attribute__((aligned(256))) uint16_t scrap_lds[4 * 128];         // 256 bytes per wave, write-only
+  uint16_t* const k_lds = lds;
+  uint16_t* const v_lds = lds + 2 * kTileElems64;
 
   // Workgroups are dispatched round-robin over the 8 XCDs (each with its own L2) in linear
   // block order.  All query tiles that read the same K/V -- one (sequence, kv head) -- are
@@ -90,22 +115,29 @@ __global__ __launch_bounds__(kPfThreads, 2) void prefill_chunk_kernel(
   qt = n_qt - 1 - qt;                                              // later tiles see more keys: start them first
   const int slot = unit % gridDim.y;
   const int r = unit / gridDim.y;
+  const int tid = threadIdx.x;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);      // uniform: block ids and LDS bases stay scalar
+  // Everything the first tile's addresses depend on is fetched in one round trip: the chunk bounds, the context
+  // length and -- on the guess that the sequence has that many blocks -- the id of this wave's first KV block.
+  const int32_t* __restrict__ table = block_table + (size_t)r * max_blocks_per_seq;
   const int q_begin = cu_q_lens[r];
-  const int lq = cu_q_lens[r + 1] - q_begin;
+  const int q_end = cu_q_lens[r + 1];
+  const int s_raw = seq_lens[r];
+  const int32_t guessed_id = table[min(wave, max_blocks_per_seq - 1)];
+  asm volatile("" ::: "memory");                                   // keep the four loads together, ahead of their first use
+  const int lq = q_end - q_begin;
   if (qt * kTokensPerWg >= lq) return;                             // uniform over the workgroup
   const int group = num_q_heads / num_kv_heads;
   const int subs = group / HW;                                     // workgroups per kv head
   const int kvh = slot / subs;
   const int sub = slot % subs;
-  const int s_len = min(max(seq_lens[r], 0), max_blocks_per_seq * kBlockSize);
+  const int s_len = min(max(s_raw, 0), max_blocks_per_seq * kBlockSize);
   const int p0 = max(s_len - lq, 0);                               // absolute position of chunk token 0
-  const int32_t* __restrict__ table = block_table + (size_t)r * max_blocks_per_seq;
 
-  const int tid = threadIdx.x;
-  const int wave = tid >> 6;
   const int lane = tid & 63;
   const int col = lane & 31;       // query row within the wave (MFMA column index)
   const int hg = lane >> 5;        // lane half: contraction slots 8*hg .. 8*hg+7
+  const int kswz = hg ^ (col & 15);   // K chunk 2 ks + hg of this lane's row sits at position kswz ^ 2 ks
   const int h = kvh * group + sub * HW + wave % HW;                // this wave's query head
   const int tok0 = qt * kTokensPerWg + (wave / HW) * kPfRows;      // its first chunk token
   const bool wave_has_rows = tok0 < lq;
@@ -115,11 +147,16 @@ __global__ __launch_bounds__(kPfThreads, 2) void prefill_chunk_kernel(
   const int wg_kv_end = min(s_len, p0 + min(lq, qt * kTokensPerWg + kTokensPerWg));
   const int wave_kv_end = wave_has_rows ? min(s_len, p0 + min(lq, tok0 + kPfRows)) : 0;
 
-  u32x4 qf[8];
-  {
-    const uint16_t* src = q + ((size_t)(q_begin + min(i_row, lq - 1)) * num_q_heads + h) * kHeadDim + hg * 8;
+  // The wave's 32 q rows (8 KiB) go global -> LDS -> registers: fetched as whole 256-byte rows (4 rows per load
+  // instruction, every cache line used in full), parked in the tile buffers that the second tile will overwrite
+  // later, with the chunk permutation of the K tiles, then read in the B-operand layout of the first product.
+  u32x4 qf[8];                                                      // Q^T operand, filled once the rows are in LDS
+  uint16_t* const q_park = (wave < 2 ? k_lds : v_lds) + kTileElems64 + (wave & 1) * (kPfRows * kHeadDim);
 #pragma unroll
-    for (int ks = 0; ks < 8; ++ks) qf[ks] = *reinterpret_cast<const u32x4*>(src + ks * 16);
+  for (int i = 0; i < 8; ++i) {
+    const int j = 4 * i + (lane >> 4);                                                   // row of the wave's 32
+    const uint16_t* src = q + ((size_t)(q_begin + min(tok0 + j, lq - 1)) * num_q_heads + h) * kHeadDim;
+    lds_dma16(src + (((lane & 15) ^ (j & 15)) * 8), q_park + i * 4 * kHeadDim);
   }
 
   f32x16 oacc[4];
@@ -130,43 +167,53 @@ __global__ __launch_bounds__(kPfThreads, 2) void prefill_chunk_kernel(
   float m_run = -INFINITY;         // running maximum of the scaled logits (log2 domain)
   float l_run = 0.f;               // running sum; this lane half's keys only
 
-  // Staging registers of the next tile: 4 x 16 bytes of K and of V per thread.  Piece i of a
-  // thread lies in KV block (k0/16 + i) for every thread, so the 4 block ids of a tile are
-  // wave-uniform; they are looked up one tile ahead of the loads that need them.
-  // Loads are unconditional (no branch around them keeps the hardware load counter exact, so
-  // waiting for one register set never drains the other): a key the workgroup cannot see is
-  // replaced by the last key it can see, whose rows are real, finite and already in cache; its
-  // weight is zero through the causal mask.
-  const int kv_last = wg_kv_end - 1;                               // >= 0 here
+  // Tile loads.  Wave w brings KV block (k0/16 + w) into rows 16w .. 16w+15 of the K and V buffers: load i
+  // of a wave fills rows 16w + 4i .. +3, lane l row 4i + l/16 of the block, chunk position l%16.  The block id
+  // is wave-uniform and is looked up one tile ahead of the loads that need it.  A key the workgroup cannot see
+  // is replaced by the last key it can see, whose rows are real, finite and already in cache; its weight is
+  // zero through the causal mask.
+  const int kv_last = max(wg_kv_end - 1, 0);
   const int last_block = kv_last / kBlockSize;
-  auto lookup = [&](int32_t (&ids)[4], int k0) {
-#pragma unroll
-    for (int i = 0; i < 4; ++i) ids[i] = table[min(k0 / kBlockSize + i, last_block)];
-  };
-  auto fetch = [&](u32x4 (&kst)[4], u32x4 (&vst)[4], const int32_t (&ids)[4], int k0) {
-#pragma unroll
-    for (int i = 0; i < 4; ++i) {
-      const int id = tid + kPfThreads * i;                         // 16-byte piece of the 64 x 128 tile
-      const int key = min(k0 + (id >> 4), kv_last);                // in block ids[i]
-      const size_t off = (((size_t)ids[i] * num_kv_heads + kvh) * kBlockSize + (key & 15)) * kHeadDim + (id & 15) * 8;
-      kst[i] = *reinterpret_cast<const u32x4*>(k_cache + off);
-      vst[i] = *reinterpret_cast<const u32x4*>(v_cache + off);
-    }
-  };
-  auto stage = [&](const u32x4 (&kst)[4], const u32x4 (&vst)[4], int buf) {
+  auto lookup = [&](int k0) { return table[min(k0 / kBlockSize + wave, last_block)]; };
+  const int pos16 = lane & 15;                                     // chunk position inside the LDS row
+  const int row4 = lane >> 4;
+  auto issue = [&](int k0, int buf, int32_t block_id) {
+    const size_t block_base = ((size_t)block_id * num_kv_heads + kvh) * kBlockSize;
+    uint16_t* const kdst = k_lds + buf * kTileElems64 + wave * (kBlockSize * kHeadDim);
+    uint16_t* const vdst = v_lds + buf * kTileElems64 + wave * (kBlockSize * kHeadDim);
 #pragma unroll
     for (int i = 0; i < 4; ++i) {
-      const int id = tid + kPfThreads * i;
-      *reinterpret_cast<u32x4*>(&k_lds[buf][(id >> 4) * kPitchK + (id & 15) * 8]) = kst[i];
-      *reinterpret_cast<u32x4*>(&v_lds[buf][(id >> 4) * kPitchV + (id & 15) * 8]) = vst[i];
+      const int row = 4 * i + row4;                                // row of the block = LDS row & 15
+      const int key = min(k0 + wave * kBlockSize + row, kv_last);
+      const size_t grow = (block_base + (key & 15)) * kHeadDim;
+      const int ck = pos16 ^ row;                                  // K: chunk c sits at position c ^ (r & 15)
+      const int cv = pos16 ^ (4 * row4);                           // V: chunk c sits at position c ^ 4 (r & 3)
+      lds_dma16(k_cache + grow + ck * 8, kdst + i * 4 * kHeadDim);
+      lds_dma16(v_cache + grow + cv * 8, vdst + i * 4 * kHeadDim);
     }
+  };
+  // Warm the L2 for the tile after the next one: the wave's KV block is 4 KiB of K and 4 KiB of V = 64 lines of
+  // 128 bytes, one per lane, fetched as 4-byte global-to-LDS loads into a scrap area that nobody reads.
+  auto touch = [&](int32_t block_id) {
+    const size_t block_base = ((size_t)block_id * num_kv_heads + kvh) * kBlockSize * kHeadDim;
+    lds_dma4((lane < 32 ? k_cache : v_cache) + block_base + (lane & 31) * 64, scrap_lds + wave * 128);
+  };
+  // This wave's tile loads have landed in LDS (the touch issued after them may still be under way), then every
+  // wave's have, and every wave is done with the other buffer.
+  auto tiles_ready = [&]() {
+    asm volatile("s_waitcnt vmcnt(1)" ::: "memory");
+    __syncthreads();
+  };
+  auto first_tile_ready = [&]() {                                  // nothing was issued after the tile's loads
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+    __syncthreads();
   };
 
   // ---- one tile of work for this wave, from LDS buffer `buf`
   auto compute = [&](int k0, int buf) {
     if (k0 < wave_kv_end) {
-      const uint16_t* ks_tile = k_lds[buf];
-      const uint16_t* vs_tile = v_lds[buf];
+      const uint16_t* ks_tile = k_lds + buf * kTileElems64;
+      const uint16_t* vs_tile = v_lds + buf * kTileElems64;
       // ---- S^T = K . Q^T
       f32x16 sacc[2];
 #pragma unroll
@@ -175,7 +222,7 @@ __global__ __launch_bounds__(kPfThreads, 2) void prefill_chunk_kernel(
         for (int v = 0; v < 16; ++v) sacc[sb][v] = 0.f;
 #pragma unroll
         for (int ks = 0; ks < 8; ++ks) {
-          const u32x4 kf = *reinterpret_cast<const u32x4*>(&ks_tile[(sb * 32 + col) * kPitchK + ks * 16 + hg * 8]);
+          const u32x4 kf = *reinterpret_cast<const u32x4*>(&ks_tile[(sb * 32 + col) * kHeadDim + ((kswz ^ (2 * ks)) * 8)]);
           sacc[sb] = mfma32<T>(kf, qf[ks], sacc[sb]);
         }
       }
@@ -226,17 +273,20 @@ __global__ __launch_bounds__(kPfThreads, 2) void prefill_chunk_kernel(
           for (int v = 0; v < 16; ++v) oacc[db][v] *= alpha;
       }
       // ---- O^T += V^T . P^T
-      const int tr_row = (lane & 15) >> 2;                          // which of the 4 keys this lane addresses
-      const int tr_col = 16 * ((lane >> 4) & 1) + 4 * (lane & 3);  // and which 4-dim group
+      // lane -> (key tr_row of 4, 4-dim group tr_col of 32 dims): chunk 4 db + tr_col / 8 of the row, moved by
+      // the V permutation to 4 (db ^ tr_row) + tr_col / 8
+      const int tr_row = (lane & 15) >> 2;
+      const int tr_col = 16 * ((lane >> 4) & 1) + 4 * (lane & 3);
 #pragma unroll
       for (int sb = 0; sb < 2; ++sb)
 #pragma unroll
         for (int t = 0; t < 2; ++t) {
-          const uint16_t* vrow = vs_tile + (sb * 32 + 16 * t + 4 * hg + tr_row) * kPitchV + tr_col;
+          const uint16_t* vrow = vs_tile + (sb * 32 + 16 * t + 4 * hg + tr_row) * kHeadDim + tr_col;
 #pragma unroll
           for (int db = 0; db < 4; ++db) {
-            const u32x2 lo = lds_read_tr16(vrow + db * 32);                    // keys 16t+4hg+0..3
-            const u32x2 hi = lds_read_tr16(vrow + 8 * kPitchV + db * 32);      // keys 16t+8+4hg+0..3
+            const int dofs = 32 * (db ^ tr_row);
+            const u32x2 lo = lds_read_tr16(vrow + dofs);                       // keys 16t+4hg+0..3
+            const u32x2 hi = lds_read_tr16(vrow + 8 * kHeadDim + dofs);        // keys 16t+8+4hg+0..3
             oacc[db] = mfma32<T>(u32x4{lo[0], lo[1], hi[0], hi[1]}, pb[sb][t], oacc[db]);
           }
         }
@@ -244,44 +294,33 @@ __global__ __launch_bounds__(kPfThreads, 2) void prefill_chunk_kernel(
 
   };
 
-  // Software pipeline over key tiles: while tile kt is used from LDS, tile kt+1 sits in one
-  // register set (loads issued a whole tile earlier) and the loads of tile kt+2 are issued
-  // into the other, so a load has two tile-times to arrive.  Block ids run one tile ahead of
-  // the loads that use them.
+  // Pipeline over key tiles: while tile kt is used from one LDS buffer, the loads of tile kt+1 fill the other.
+  // One barrier per tile: behind it every wave's part of tile kt+1 is in LDS and nobody reads tile kt any more.
   const int n_tiles = (wg_kv_end + kPfKTile - 1) / kPfKTile;
-  u32x4 ka[4], va[4], kb[4], vb[4];
-  int32_t ids[4];
-  lookup(ids, 0);
-  fetch(ka, va, ids, 0);
-  lookup(ids, kPfKTile);
-  stage(ka, va, 0);
-  __syncthreads();
-  fetch(ka, va, ids, kPfKTile);
-  lookup(ids, 2 * kPfKTile);
-  for (int kt = 0; kt < n_tiles; kt += 2) {
-    // even tile: in LDS buffer 0; tile kt+1 in flight in set a
-    fetch(kb, vb, ids, (kt + 2) * kPfKTile);
-    lookup(ids, (kt + 3) * kPfKTile);
-    compute(kt * kPfKTile, 0);
-    if (kt + 1 >= n_tiles) break;
-    stage(ka, va, 1);
-    __syncthreads();               // tile kt fully consumed by all waves, tile kt+1 visible
-    // odd tile: in LDS buffer 1; tile kt+2 in flight in set b
-    fetch(ka, va, ids, (kt + 3) * kPfKTile);
-    lookup(ids, (kt + 4) * kPfKTile);
-    compute((kt + 1) * kPfKTile, 1);
-    if (kt + 2 >= n_tiles) break;
-    stage(kb, vb, 0);
-    __syncthreads();
+  issue(0, 0, wave <= last_block ? guessed_id : table[last_block]);
+  int32_t id1 = lookup(kPfKTile), id2 = lookup(2 * kPfKTile);       // block ids of the next two tiles
+  first_tile_ready();
+#pragma unroll
+  for (int ks = 0; ks < 8; ++ks)
+    qf[ks] = *reinterpret_cast<const u32x4*>(&q_park[col * kHeadDim + ((kswz ^ (2 * ks)) * 8)]);
+  __syncthreads();                                                 // every wave holds its q before tile 1 lands there
+  for (int kt = 0; kt < n_tiles; ++kt) {
+    if (kt + 1 < n_tiles) issue((kt + 1) * kPfKTile, (kt + 1) & 1, id1);
+    touch(id2);                                                    // unconditional: exactly one load follows the tile's
+    id1 = id2;
+    id2 = lookup((kt + 3) * kPfKTile);
+    compute(kt * kPfKTile, kt & 1);
+    tiles_ready();
   }
+  asm volatile("s_waitcnt vmcnt(0)" ::: "memory");                 // no load may still be writing LDS when the wave ends
 
   // ---- epilogue: normalise, round, and turn the wave's O^T (a query row per lane) into whole
   // 256-byte output rows through a private 32 x 128 LDS patch, so that the global stores are
   // 16 bytes per lane and contiguous per row.
   l_run += __shfl_xor(l_run, 32);
-  __syncthreads();                                                 // every wave is done reading the K tiles
+  // (the last tiles_ready() left every wave done with the tile buffers)
   if (wave_has_rows) {
-    uint16_t* patch = &k_lds[0][0] + wave * (kPfRows * kPitchK);   // 4 patches fill the two K buffers exactly
+    uint16_t* patch = lds + wave * (kPfRows * kPitchO);
     const float inv = l_run > 0.f ? 1.f / l_run : 0.f;
 #pragma unroll
     for (int db = 0; db < 4; ++db)
@@ -290,13 +329,13 @@ __global__ __launch_bounds__(kPfThreads, 2) void prefill_chunk_kernel(
         u32x2 o;
         o[0] = pack2<T>(oacc[db][4 * j] * inv, oacc[db][4 * j + 1] * inv);
         o[1] = pack2<T>(oacc[db][4 * j + 2] * inv, oacc[db][4 * j + 3] * inv);
-        *reinterpret_cast<u32x2*>(&patch[col * kPitchK + db * 32 + 8 * j + 4 * hg]) = o;
+        *reinterpret_cast<u32x2*>(&patch[col * kPitchO + db * 32 + 8 * j + 4 * hg]) = o;
       }
     // LDS operations of one wave complete in order: the reads below see the writes above
 #pragma unroll
     for (int i = 0; i < 8; ++i) {
       const int row = 4 * i + (lane >> 4);
-      const u32x4 v = *reinterpret_cast<const u32x4*>(&patch[row * kPitchK + (lane & 15) * 8]);
+      const u32x4 v = *reinterpret_cast<const u32x4*>(&patch[row * kPitchO + (lane & 15) * 8]);
       if (tok0 + row < lq)
         *reinterpret_cast<u32x4*>(out + ((size_t)(q_begin + tok0 + row) * num_q_heads + h) * kHeadDim + (lane & 15) * 8) = v;
     }
