@@ -100,19 +100,19 @@ def test_gathered_slots_are_bit_exact(torch):
 
 
 # -------------------------------------------------------------------- decode
-def _decode_case(torch, seq_lens, hq, hkv, dtype, seed, poison=False, min_row_len=0):
+def _decode_case(torch, seq_lens, hq, hkv, dtype, seed, poison=False, min_row_len=0, scale=SCALE):
     rng = np.random.default_rng(seed)
     table, nb = make_block_table(rng, seq_lens, 16, min_row_len=min_row_len)
     q, k, v = make_qkv_numpy(rng, len(seq_lens), hq, hkv, 128, nb, 16, dtype)
     if poison:
         poison_unused_rows(k, table, seq_lens, NAN_BITS[dtype])
         poison_unused_rows(v, table, seq_lens, NAN_BITS[dtype])
-    p = vtc.make_params(hq, hkv, 128, 16, table.shape[1], dtype, SCALE)
+    p = vtc.make_params(hq, hkv, 128, 16, table.shape[1], dtype, scale)
     out = vtc.vtc_attn_decode(p, bits_to_tensor(q, dtype), bits_to_tensor(k, dtype), bits_to_tensor(v, dtype),
                               _i32(torch, table), _i32(torch, seq_lens))
     torch.cuda.synchronize()
     got = OA.widen(tensor_to_bits(out), dtype)
-    want = OA.paged_decode(q, k, v, table, seq_lens, SCALE, dtype)
+    want = OA.paged_decode(q, k, v, table, seq_lens, scale, dtype)
     return got, want
 
 
@@ -250,7 +250,7 @@ def test_decode_full_size_configs_on_sampled_rows(torch, cfg):
 
 
 # ------------------------------------------------------------------- prefill
-def _prefill_case(torch, q_lens, seq_lens, hq, hkv, dtype, seed, poison=False):
+def _prefill_case(torch, q_lens, seq_lens, hq, hkv, dtype, seed, poison=False, scale=SCALE):
     rng = np.random.default_rng(seed)
     table, nb = make_block_table(rng, seq_lens, 16)
     cu = np.concatenate([[0], np.cumsum(q_lens)]).astype(np.int32)
@@ -258,13 +258,13 @@ def _prefill_case(torch, q_lens, seq_lens, hq, hkv, dtype, seed, poison=False):
     if poison:
         poison_unused_rows(k, table, seq_lens, NAN_BITS[dtype])
         poison_unused_rows(v, table, seq_lens, NAN_BITS[dtype])
-    p = vtc.make_params(hq, hkv, 128, 16, table.shape[1], dtype, SCALE)
+    p = vtc.make_params(hq, hkv, 128, 16, table.shape[1], dtype, scale)
     out = vtc.vtc_attn_prefill_chunk(p, bits_to_tensor(q, dtype), _i32(torch, cu), int(max(q_lens)),
                                      bits_to_tensor(k, dtype), bits_to_tensor(v, dtype), _i32(torch, table),
                                      _i32(torch, seq_lens))
     torch.cuda.synchronize()
     got = OA.widen(tensor_to_bits(out), dtype)
-    want = OA.paged_prefill_chunk(q, cu, k, v, table, seq_lens, SCALE, dtype)
+    want = OA.paged_prefill_chunk(q, cu, k, v, table, seq_lens, scale, dtype)
     return got, want
 
 
@@ -279,6 +279,36 @@ def test_prefill_chunk_ragged_matches_the_oracle(torch, dtype, hq, hkv):
     err = np.abs(got - want)
     say(f"  max abs err {err.max():.3e}  max |o| {np.abs(want).max():.3f}")
     assert within_tolerance(got, want, dtype)
+
+
+@pytest.mark.parametrize("scale", [-0.07, 0.0, 0.4])
+@pytest.mark.parametrize("dtype,hq,hkv", [("f16", 4, 4), ("bf16", 8, 2)])
+def test_negative_zero_and_large_scales(torch, scale, dtype, hq, hkv):
+    # the scale is the caller's: a negative one turns the softmax towards the smallest logits, zero makes every
+    # visible key weigh the same, a large one lets a single key dominate; MHA (vector path) and GQA (matrix path)
+    say(f"scale {scale} dtype={dtype} Hq={hq} Hkv={hkv}")
+    got, want = _decode_case(torch, [1, 17, 100, 300, 0, 64], hq, hkv, dtype, seed=51, scale=scale)
+    say(f"  decode max abs err {np.abs(got - want).max():.3e}")
+    assert within_tolerance(got, want, dtype)
+    got, want = _prefill_case(torch, [5, 70, 33], [5, 150, 33], hq, hkv, dtype, seed=52, scale=scale)
+    say(f"  prefill max abs err {np.abs(got - want).max():.3e}")
+    assert within_tolerance(got, want, dtype)
+
+
+def test_decode_at_the_capacity_of_the_block_table(torch):
+    # a context that fills every block of its table row, and one beyond it: lengths are clamped to the capacity
+    say("decode at block-table capacity")
+    rng = np.random.default_rng(53)
+    cap = 5 * 16
+    table, nb = make_block_table(rng, [cap, cap, 7], 16)
+    assert table.shape[1] == 5
+    q, k, v = make_qkv_numpy(rng, 3, 8, 2, 128, nb, 16, "f16")
+    p = vtc.make_params(8, 2, 128, 16, 5, "f16", SCALE)
+    out = vtc.vtc_attn_decode(p, bits_to_tensor(q, "f16"), bits_to_tensor(k, "f16"), bits_to_tensor(v, "f16"),
+                              _i32(torch, table), _i32(torch, [cap, cap + 1000, 7]))
+    torch.cuda.synchronize()
+    want = OA.paged_decode(q, k, v, table, [cap, cap, 7], SCALE, "f16")
+    assert within_tolerance(OA.widen(tensor_to_bits(out), "f16"), want, "f16")
 
 
 @pytest.mark.parametrize("chunk", [0, 1])
