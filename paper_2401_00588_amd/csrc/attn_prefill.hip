@@ -38,6 +38,17 @@ using bf16x8 = __bf16 __attribute__((ext_vector_type(8)));
 using s16x4 = short __attribute__((ext_vector_type(4)));
 using u32x2 = uint32_t __attribute__((ext_vector_type(2)));
 
+#ifndef VTC_PREFILL_SCHED_HINTS
+#define VTC_PREFILL_SCHED_HINTS 1
+#endif
+#ifndef VTC_PREFILL_QK_AHEAD
+#define VTC_PREFILL_QK_AHEAD 6
+#endif
+constexpr int kQkAhead = VTC_PREFILL_QK_AHEAD;   // K fragments in flight ahead of the product that uses them
+#ifndef VTC_PREFILL_PV_AHEAD
+#define VTC_PREFILL_PV_AHEAD 4
+#endif
+constexpr int kPvAhead = VTC_PREFILL_PV_AHEAD;   // V^T fragments in flight ahead of the product that uses them
 constexpr int kXcds = 8;                 // accelerator complex dies of an MI355X
 constexpr int kPfThreads = 256;
 constexpr int kPfRows = 32;              // query rows per wave
@@ -226,6 +237,16 @@ __global__ __launch_bounds__(kPfThreads, 2) void prefill_chunk_kernel(
           sacc[sb] = mfma32<T>(kf, qf[ks], sacc[sb]);
         }
       }
+#if VTC_PREFILL_SCHED_HINTS
+      // order of the 16 fragment reads and 16 products above: reads run kQkAhead fragments ahead of their use
+      __builtin_amdgcn_sched_group_barrier(0x100, kQkAhead, 0);
+#pragma unroll
+      for (int i = 0; i < 16 - kQkAhead; ++i) {
+        __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+        __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
+      }
+      __builtin_amdgcn_sched_group_barrier(0x008, kQkAhead, 0);
+#endif
       // ---- causal mask (only tiles that reach past the wave's first query position), row maximum
       const float masked = kPosScale ? -INFINITY : INFINITY;
       if (k0 + kPfKTile - 1 > p0 + tok0) {
@@ -290,6 +311,17 @@ __global__ __launch_bounds__(kPfThreads, 2) void prefill_chunk_kernel(
             oacc[db] = mfma32<T>(u32x4{lo[0], lo[1], hi[0], hi[1]}, pb[sb][t], oacc[db]);
           }
         }
+#if VTC_PREFILL_SCHED_HINTS
+      // order of the 32 transposing reads and 16 products above: kPvAhead fragments (2 reads each) ahead of use;
+      // the first reads may start while the weights are still being exponentiated
+      __builtin_amdgcn_sched_group_barrier(0x100, 2 * kPvAhead, 0);
+#pragma unroll
+      for (int i = 0; i < 16 - kPvAhead; ++i) {
+        __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+        __builtin_amdgcn_sched_group_barrier(0x100, 2, 0);
+      }
+      __builtin_amdgcn_sched_group_barrier(0x008, kPvAhead, 0);
+#endif
     }
 
   };
