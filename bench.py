@@ -115,6 +115,21 @@ def cpu_baseline(st, scale, sample_requests):
     else:
         secs = run()
     kv_bytes = sum(seq) * sh.kv_bytes_per_token
+    # the small correctness configuration on one core, for scale (8 requests, ~18 MB of KV, host-generated inputs)
+    from workloads import make_qkv_numpy, make_block_table, make_step_batch
+    b1 = make_step_batch(1)
+    rng1 = np.random.default_rng(1)
+    table1, nb1 = make_block_table(rng1, b1.seq_lens, b1.shape.block_size)
+    q1, k1, v1 = make_qkv_numpy(rng1, b1.num_decode, b1.shape.num_q_heads, b1.shape.num_kv_heads, b1.shape.head_dim,
+                                nb1, b1.shape.block_size, b1.shape.dtype)
+    t0 = time.perf_counter()
+    if threadpool_limits is not None:
+        with threadpool_limits(limits=1):
+            OA.paged_decode(q1, k1, v1, table1, b1.seq_lens, scale, b1.shape.dtype)
+    else:
+        OA.paged_decode(q1, k1, v1, table1, b1.seq_lens, scale, b1.shape.dtype)
+    secs1 = time.perf_counter() - t0
+    kv1 = int(sum(int(x) for x in b1.seq_lens)) * b1.shape.kv_bytes_per_token
     return {
         "value": kv_bytes / secs / 1e9,
         "unit": "GB/s",
@@ -123,6 +138,8 @@ def cpu_baseline(st, scale, sample_requests):
         "sample": f"{len(picks)} of {b.num_decode} decode requests x all {sh.num_q_heads} q heads "
                   f"({sum(seq)} context tokens, {kv_bytes / 1e6:.1f} MB of KV), fp64 numpy, {secs:.2f} s",
         "seconds": secs,
+        "one_core_cfg1": {"seconds": round(secs1, 4), "value": round(kv1 / secs1 / 1e9, 4), "unit": "GB/s",
+                          "sample": f"cfg1: {b1.num_decode} requests, {kv1 / 1e6:.1f} MB of KV, 1 thread"},
     }
 
 
