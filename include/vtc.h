@@ -5,9 +5,13 @@
  *
  * Paper: "Fairness in Serving Large Language Models" (arXiv 2401.00588).
  * One iteration of the execution stream of Algorithm 2 calls
- *     forward_prefill(B_new)  ->  vtc_attn_prefill_chunk   (attention part)
- *     forward_decode(B)       ->  vtc_attn_decode          (attention part)
- *     c_i += ...              ->  vtc_counter_update
+ *     (new tokens' K/V into the cache)  ->  vtc_kv_append
+ *     forward_prefill(B_new)            ->  vtc_attn_prefill_chunk   (attention part)
+ *     forward_decode(B)                 ->  vtc_attn_decode          (attention part)
+ *     c_i += ...                        ->  vtc_counter_update
+ *     the last two in one call          ->  vtc_step_decode
+ * and the variants of the charge: vtc_counter_update_cost (Algorithm 4, general cost function;
+ * weighted VTC), vtc_counter_update_predicted (Algorithm 3, length prediction).
  * The paper names a paged KV cache as its substrate (Section 5.1) and gives no
  * attention formula; the kernels compute standard scaled dot-product softmax
  * attention (see each entry point).
@@ -291,8 +295,9 @@ int vtc_kv_append(const vtc_attn_params* params /*[host]*/, int32_t num_seqs, co
  *     slot(r,p) = block_table[r][p / block_size] * block_size + p % block_size
  * to slots_out[cu_out[r] + p].  cu_out [device] int32 [num_seqs+1] are the
  * exclusive prefix sums of seq_lens; max_seq_len is a host-side upper bound on
- * seq_lens (sizes the launch).  Uses the same index helper as the attention
- * kernels.
+ * seq_lens (sizes the launch).  The attention kernels address whole blocks
+ * (block_table[r][b] times the block stride), which is this formula at
+ * p = b * block_size; vtc_kv_append addresses single rows with it.
  */
 int vtc_debug_gather_slots(const vtc_attn_params* params /*[host]*/, int32_t num_seqs,
                            const int32_t* block_table, const int32_t* seq_lens,

@@ -24,7 +24,7 @@ int device_cu_count() {
 
 extern "C" {
 
-int vtc_version(void) { return 210; }
+int vtc_version(void) { return 300; }   // 0.3.0
 
 const char* vtc_strerror(int code) {
   switch (code) {

@@ -29,8 +29,8 @@ __global__ __launch_bounds__(kAppendThreads) void kv_append_kernel(
     const int p = s_len - n_new + i;                                   // absolute position
     if (p < 0) continue;                                               // seq_lens shorter than the append: nothing to place
     const size_t src = ((size_t)(first + i) * num_kv_heads + head) * kHeadDim + c16 * 8;
-    const size_t dst = (((size_t)block_table[(size_t)r * max_blocks_per_seq + p / kBlockSize] * num_kv_heads + head) * kBlockSize +
-                        p % kBlockSize) * kHeadDim + c16 * 8;
+    const int32_t slot = slot_of(block_table + (size_t)r * max_blocks_per_seq, p);   // physical block * 16 + row
+    const size_t dst = (((size_t)(slot / kBlockSize) * num_kv_heads + head) * kBlockSize + slot % kBlockSize) * kHeadDim + c16 * 8;
     *reinterpret_cast<u32x4*>(k_cache + dst) = *reinterpret_cast<const u32x4*>(k_new + src);
     *reinterpret_cast<u32x4*>(v_cache + dst) = *reinterpret_cast<const u32x4*>(v_new + src);
   }

@@ -351,6 +351,34 @@ def test_prefill_config5_chunks_on_sampled_rows_and_decode_consistency(torch, ch
     assert diff <= 2 * TOL[sh.dtype]
 
 
+# ------------------------------------------------------------- random shapes
+@pytest.mark.parametrize("seed", range(10))
+def test_decode_and_prefill_on_random_small_shapes(torch, seed):
+    # seeded draws over what the fixed cases do not cross: group size x dtype x batch size x length mix
+    # (empty sequences, single tokens, lengths on and off block and tile boundaries) x block-table width
+    rng = np.random.default_rng(9000 + seed)
+    hkv = int(rng.choice([1, 2, 4, 8]))
+    group = int(rng.choice([1, 2, 4, 8]))
+    dtype = str(rng.choice(["f16", "bf16"]))
+    n = int(rng.integers(1, 40))
+    kinds = rng.integers(0, 5, size=n)
+    seq = np.where(kinds == 0, 0, np.where(kinds == 1, rng.integers(1, 4, size=n),
+                   np.where(kinds == 2, 16 * rng.integers(1, 9, size=n), rng.integers(1, 200, size=n)))).astype(np.int32)
+    say(f"random shapes seed {seed}: Hq={hkv * group} Hkv={hkv} {dtype} n={n} lens {seq.min()}..{seq.max()}")
+    got, want = _decode_case(torch, seq, hkv * group, hkv, dtype, seed=9100 + seed, poison=True,
+                             min_row_len=int(rng.integers(0, 30)))
+    say(f"  decode max abs err {np.abs(got - want).max():.3e}")
+    assert within_tolerance(got, want, dtype)
+    assert (got[seq == 0] == 0).all()
+    # prefill: chunks of random length ending anywhere in a context of random length
+    m = int(rng.integers(1, 6))
+    q_lens = rng.integers(1, 100, size=m).astype(np.int32)
+    ctx = (q_lens + rng.integers(0, 150, size=m) * rng.integers(0, 2, size=m)).astype(np.int32)
+    got, want = _prefill_case(torch, q_lens, ctx, hkv * group, hkv, dtype, seed=9200 + seed, poison=True)
+    say(f"  prefill q_lens {q_lens.tolist()} ctx {ctx.tolist()} max abs err {np.abs(got - want).max():.3e}")
+    assert within_tolerance(got, want, dtype)
+
+
 # ---------------------------------------------------------------- whole step
 def test_mixed_step_config5_on_one_stream(torch):
     say("mixed step: prefill chunk + decode + one counter update")
