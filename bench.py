@@ -260,7 +260,7 @@ def main() -> int:
     value = kv_bytes / (ms_per_step * 1e-3) / 1e9
     achieved = kv_bytes / (kernel_avg_ms * 1e-3) / 1e9
     line = {
-        "metric": "decode attention KV GB/s over one VTC serving step (1 GPU)",
+        "metric": "decode attention KV GB/s (% of HBM peak) + batch tokens/s per step, 1 GPU",
         "value": round(value, 2),
         "unit": "GB/s",
         "n_gpus": 1,
