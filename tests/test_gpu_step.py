@@ -151,3 +151,48 @@ def test_step_decode_on_the_config_batches(torch, cfg):
         worst = max(worst, float(np.abs(got[r, h] - want).max()))
     say(f"  worst sampled err {worst:.3e}")
     assert worst <= TOL[sh.dtype]
+
+
+def test_step_decode_replays_from_a_hip_graph(torch):
+    # a serving loop may capture the step once and replay it: the call must be capturable (no allocation, no
+    # synchronisation, nothing that depends on state from capture time) and every replay must redo all of it
+    say("step_decode captured into a graph and replayed")
+    rng = np.random.default_rng(950)
+    seq = [3, 40, 257, 0, 700, 16]
+    hq, hkv, dtype, clients = 8, 2, "bf16", 4
+    table, nb = make_block_table(rng, seq, 16)
+    q, k, v = make_qkv_numpy(rng, len(seq), hq, hkv, 128, nb, 16, dtype)
+    ids = rng.integers(0, clients, size=len(seq)).astype(np.int32)
+    n_out = np.ones(len(seq), dtype=np.int32)
+    p = vtc.make_params(hq, hkv, 128, 16, table.shape[1], dtype, SCALE)
+    qd, kd, vd = bits_to_tensor(q, dtype), bits_to_tensor(k, dtype), bits_to_tensor(v, dtype)
+    td, sd, idd, nd = _i32(torch, table), _i32(torch, seq), _i32(torch, ids), _i32(torch, n_out)
+    counters = _i64(torch, np.zeros(clients, dtype=np.int64))
+    out = torch.empty_like(qd)
+    ws = torch.empty(vtc.vtc_attn_workspace_bytes(p, len(seq), 0), dtype=torch.uint8, device="cuda")
+
+    def step():
+        vtc.vtc_step_decode(p, qd, kd, vd, td, sd, counters, idd, None, nd, 1, 2, out=out, workspace=ws)
+
+    step()                                   # eager once: first-call set-up happens outside the capture
+    torch.cuda.synchronize()
+    eager = out.clone()
+    want = OA.paged_decode(q, k, v, table, seq, SCALE, dtype)
+    assert within_tolerance(OA.widen(tensor_to_bits(eager), dtype), want, dtype)
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        step()
+    torch.cuda.synchronize()
+    charges = 1                              # the eager call; capture itself executes nothing
+    for replay in range(3):
+        out.fill_(float("nan"))              # eager work between the replays
+        kd_sum = float(kd.float().sum().item())
+        assert np.isfinite(kd_sum)
+        graph.replay()
+        torch.cuda.synchronize()
+        charges += 1
+        assert torch.equal(out.view(torch.int16), eager.view(torch.int16)), f"replay {replay} differs from eager"
+        want_c = [0] * clients
+        for _ in range(charges):
+            want_c = counter_update(want_c, ids.tolist(), None, n_out.tolist(), 1, 2)
+        assert counters.cpu().tolist() == want_c
