@@ -766,13 +766,12 @@ static int launch_typed(const vtc_attn_params& p, int32_t num_seqs, const void* 
 
   // Grid = the waves the chip holds at once (never more, so no wave waits for a slot while
   // the others are already half way through their share).
-  static int waves_per_cu = 0;
-  if (waves_per_cu == 0) {
+  static const int waves_per_cu = [] {     // queried once per kernel instance (thread-safe static initialisation)
     int occ = 0;
     if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&occ, decode_attend_kernel<T, G, Engine>, kWave, 0) != hipSuccess || occ <= 0)
       occ = 8;
-    waves_per_cu = occ < VTC_DECODE_WAVES_PER_CU ? occ : VTC_DECODE_WAVES_PER_CU;
-  }
+    return occ < VTC_DECODE_WAVES_PER_CU ? occ : VTC_DECODE_WAVES_PER_CU;
+  }();
   long long resident = (long long)device_cu_count() * waves_per_cu;
   const int grid = (int)(resident < kMaxDecodeWaves ? resident : kMaxDecodeWaves);
 
