@@ -351,6 +351,40 @@ def test_prefill_config5_chunks_on_sampled_rows_and_decode_consistency(torch, ch
     assert diff <= 2 * TOL[sh.dtype]
 
 
+# ----------------------------------------------------------- extreme logits
+@pytest.mark.parametrize("dtype,hq,hkv", [("f16", 4, 4), ("bf16", 8, 2)])
+def test_peaked_softmax_with_large_logits(torch, dtype, hq, hkv):
+    # keys six times larger: logits spread over hundreds of units (log2 domain), so almost all weights underflow
+    # to zero and one or two keys carry the row; nothing may overflow, and rows past seq_len stay out of it
+    say(f"large logits dtype={dtype} Hq={hq} Hkv={hkv}")
+    rng = np.random.default_rng(61)
+    seq = [1, 9, 64, 300, 17]
+    table, nb = make_block_table(rng, seq, 16)
+    q, k, v = make_qkv_numpy(rng, len(seq), hq, hkv, 128, nb, 16, dtype)
+    from workloads.tensors import f32_to_storage_bits
+    k = f32_to_storage_bits((6.0 * OA.widen(k, dtype)).astype(np.float32), dtype)
+    poison_unused_rows(k, table, seq, NAN_BITS[dtype])
+    poison_unused_rows(v, table, seq, NAN_BITS[dtype])
+    p = vtc.make_params(hq, hkv, 128, 16, table.shape[1], dtype, SCALE)
+    kd, vd, td = bits_to_tensor(k, dtype), bits_to_tensor(v, dtype), _i32(torch, table)
+    out = vtc.vtc_attn_decode(p, bits_to_tensor(q, dtype), kd, vd, td, _i32(torch, seq))
+    torch.cuda.synchronize()
+    want = OA.paged_decode(q, k, v, table, seq, SCALE, dtype)
+    got = OA.widen(tensor_to_bits(out), dtype)
+    say(f"  decode max abs err {np.abs(got - want).max():.3e}  largest weight {max(OA.softmax_weights(OA.widen(q[3, 0], dtype), OA.gather_sequence(k, table[3], 300, 0, dtype), SCALE)):.3f}")
+    assert within_tolerance(got, want, dtype)
+    # the same cache as one prefill chunk per sequence (whole prompts)
+    cu = np.concatenate([[0], np.cumsum(seq)]).astype(np.int32)
+    rng2 = np.random.default_rng(62)
+    qp = f32_to_storage_bits(rng2.standard_normal((int(cu[-1]), hq, 128), dtype=np.float32), dtype)
+    outp = vtc.vtc_attn_prefill_chunk(p, bits_to_tensor(qp, dtype), _i32(torch, cu), max(seq), kd, vd, td, _i32(torch, seq))
+    torch.cuda.synchronize()
+    wantp = OA.paged_prefill_chunk(qp, cu, k, v, table, seq, SCALE, dtype)
+    gotp = OA.widen(tensor_to_bits(outp), dtype)
+    say(f"  prefill max abs err {np.abs(gotp - wantp).max():.3e}")
+    assert within_tolerance(gotp, wantp, dtype)
+
+
 # ------------------------------------------------------------- random shapes
 @pytest.mark.parametrize("seed", range(10))
 def test_decode_and_prefill_on_random_small_shapes(torch, seed):
