@@ -351,6 +351,30 @@ def test_prefill_config5_chunks_on_sampled_rows_and_decode_consistency(torch, ch
     assert diff <= 2 * TOL[sh.dtype]
 
 
+def test_prefill_chunking_is_invisible_on_the_gpu(torch):
+    # a prompt prefilled in one call or in two chunks gives the same rows: a row's keys, their tiling and the order
+    # of its online-softmax updates do not depend on where the chunk boundary falls, so the bits are equal
+    say("prefill: one chunk vs two chunks")
+    rng = np.random.default_rng(71)
+    total, first = 200, 72
+    hq, hkv, dtype = 8, 2, "bf16"
+    table, nb = make_block_table(rng, [total], 16)
+    q, k, v = make_qkv_numpy(rng, total, hq, hkv, 128, nb, 16, dtype)
+    p = vtc.make_params(hq, hkv, 128, 16, table.shape[1], dtype, SCALE)
+    kd, vd, td = bits_to_tensor(k, dtype), bits_to_tensor(v, dtype), _i32(torch, table)
+    qd = bits_to_tensor(q, dtype)
+    whole = vtc.vtc_attn_prefill_chunk(p, qd, _i32(torch, [0, total]), total, kd, vd, td, _i32(torch, [total]))
+    part0 = vtc.vtc_attn_prefill_chunk(p, qd[:first].contiguous(), _i32(torch, [0, first]), first, kd, vd, td,
+                                       _i32(torch, [first]))
+    part1 = vtc.vtc_attn_prefill_chunk(p, qd[first:].contiguous(), _i32(torch, [0, total - first]), total - first, kd,
+                                       vd, td, _i32(torch, [total]))
+    torch.cuda.synchronize()
+    assert torch.equal(whole[:first].view(torch.int16), part0.view(torch.int16))
+    assert torch.equal(whole[first:].view(torch.int16), part1.view(torch.int16))
+    want = OA.paged_prefill_chunk(q, [0, total], k, v, table, [total], SCALE, dtype)
+    assert within_tolerance(OA.widen(tensor_to_bits(whole), dtype), want, dtype)
+
+
 # ----------------------------------------------------------- extreme logits
 @pytest.mark.parametrize("dtype,hq,hkv", [("f16", 4, 4), ("bf16", 8, 2)])
 def test_peaked_softmax_with_large_logits(torch, dtype, hq, hkv):
