@@ -410,6 +410,19 @@ def test_peaked_softmax_with_large_logits(torch, dtype, hq, hkv):
 
 
 # ------------------------------------------------------------- random shapes
+@pytest.mark.parametrize("dtype,hq,hkv", [("bf16", 8, 2), ("f16", 4, 4)])
+def test_contexts_far_beyond_the_workload_lengths(torch, dtype, hq, hkv):
+    # one sequence spread over every resident wave (thousands of partial results to merge) next to tiny ones,
+    # and prefill chunks that sit at the end of long contexts
+    say(f"long contexts dtype={dtype} Hq={hq} Hkv={hkv}")
+    got, want = _decode_case(torch, [65536, 3, 40000, 1, 16], hq, hkv, dtype, seed=83)
+    say(f"  decode max abs err {np.abs(got - want).max():.3e}")
+    assert within_tolerance(got, want, dtype)
+    got, want = _prefill_case(torch, [100, 7, 33], [30000, 9001, 33], hq, hkv, dtype, seed=84)
+    say(f"  prefill max abs err {np.abs(got - want).max():.3e}")
+    assert within_tolerance(got, want, dtype)
+
+
 @pytest.mark.parametrize("seed", range(10))
 def test_decode_and_prefill_on_random_small_shapes(torch, seed):
     # seeded draws over what the fixed cases do not cross: group size x dtype x batch size x length mix
