@@ -87,11 +87,30 @@ __device__ __forceinline__ void lds_dma16(const uint16_t* src, uint16_t* dst_uni
   asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, off" ::"s"(lds_addr), "v"(src) : "memory", "m0");
 }
 
-// The 4-byte form: lane l writes LDS bytes [dst + 4 l, dst + 4 l + 4).
-__device__ __forceinline__ void lds_dma4(const uint16_t* src, uint16_t* dst_uniform) {
+// The same with a wave-uniform base address and 32-bit per-lane byte offsets, four loads at once: load i reads
+// base + o_i + 1024 i and writes LDS bytes [dst + 1024 i + 16 l, + 16) (the instruction's immediate offset moves
+// both addresses).  One KV block's K or V rows (4 KiB) are four such 1 KiB slices; the addresses cost no vector
+// arithmetic per tile.
+__device__ __forceinline__ void lds_dma16_x4(const uint16_t* base_uniform, uint32_t o0, uint32_t o1, uint32_t o2,
+                                             uint32_t o3, uint16_t* dst_uniform) {
   typedef __attribute__((address_space(3))) uint16_t lds_u16;
   const uint32_t lds_addr = __builtin_amdgcn_readfirstlane((uint32_t)(uintptr_t)(lds_u16*)dst_uniform);
-  asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dword %1, off" ::"s"(lds_addr), "v"(src) : "memory", "m0");
+  asm volatile(
+      "s_mov_b32 m0, %0\n\ts_nop 0\n\t"
+      "global_load_lds_dwordx4 %1, %5\n\t"
+      "global_load_lds_dwordx4 %2, %5 offset:1024\n\t"
+      "global_load_lds_dwordx4 %3, %5 offset:2048\n\t"
+      "global_load_lds_dwordx4 %4, %5 offset:3072" ::"s"(lds_addr),
+      "v"(o0), "v"(o1), "v"(o2), "v"(o3), "s"(base_uniform)
+      : "memory", "m0");
+}
+
+// The 4-byte form with a uniform base: lane l reads base + o and writes LDS bytes [dst + 4 l, dst + 4 l + 4).
+__device__ __forceinline__ void lds_dma4_uniform(const uint16_t* base_uniform, uint32_t o, uint16_t* dst_uniform) {
+  typedef __attribute__((address_space(3))) uint16_t lds_u16;
+  const uint32_t lds_addr = __builtin_amdgcn_readfirstlane((uint32_t)(uintptr_t)(lds_u16*)dst_uniform);
+  asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dword %1, %2" ::"s"(lds_addr), "v"(o), "s"(base_uniform)
+               : "memory", "m0");
 }
 
 template <typename T, int HW, bool kPosScale>
@@ -103,7 +122,7 @@ __global__ __launch_bounds__(kPfThreads, 2) void prefill_chunk_kernel(
   constexpr int TT = 4 / HW;                       // 32-token tiles per workgroup
   constexpr int kTokensPerWg = kPfRows * TT;
   __shared__ __attribute__((aligned(1024))) uint16_t lds[4 * kTileElems64];    // K buffers 0, 1, then V buffers 0, 1
-  __shared__ __attribute__((aligned(256))) uint16_t scrap_lds[4 * 128];         // 256 bytes per wave, write-only
+  __shared__ __attribute__((aligned(256))) uint16_t scrap_lds[4 * 256];         // 512 bytes per wave, write-only
   uint16_t* const k_lds = lds;
   uint16_t* const v_lds = lds + 2 * kTileElems64;
 
@@ -188,31 +207,43 @@ __global__ __launch_bounds__(kPfThreads, 2) void prefill_chunk_kernel(
   auto lookup = [&](int k0) { return table[min(k0 / kBlockSize + wave, last_block)]; };
   const int pos16 = lane & 15;                                     // chunk position inside the LDS row
   const int row4 = lane >> 4;
+  // per-lane byte offsets inside a (block, head) tile for the four loads of a block (see lds_dma16_x4); they do not
+  // change from tile to tile
+  uint32_t koff[4];
+#pragma unroll
+  for (int i = 0; i < 4; ++i) koff[i] = row4 * 256 + ((pos16 ^ (4 * i + row4)) * 16);   // K: chunk c at c ^ (r & 15)
+  const uint32_t voff = row4 * 256 + ((pos16 ^ (4 * row4)) * 16);                       // V: chunk c at c ^ 4 (r & 3)
   auto issue = [&](int k0, int buf, int32_t block_id) {
     const size_t block_base = ((size_t)block_id * num_kv_heads + kvh) * kBlockSize;
     uint16_t* const kdst = k_lds + buf * kTileElems64 + wave * (kBlockSize * kHeadDim);
     uint16_t* const vdst = v_lds + buf * kTileElems64 + wave * (kBlockSize * kHeadDim);
+    if (k0 + wave * kBlockSize + kBlockSize - 1 <= kv_last) {       // the whole block is visible: uniform addresses
+      lds_dma16_x4(k_cache + block_base * kHeadDim, koff[0], koff[1], koff[2], koff[3], kdst);
+      lds_dma16_x4(v_cache + block_base * kHeadDim, voff, voff, voff, voff, vdst);
+      return;
+    }
 #pragma unroll
     for (int i = 0; i < 4; ++i) {
       const int row = 4 * i + row4;                                // row of the block = LDS row & 15
       const int key = min(k0 + wave * kBlockSize + row, kv_last);
       const size_t grow = (block_base + (key & 15)) * kHeadDim;
-      const int ck = pos16 ^ row;                                  // K: chunk c sits at position c ^ (r & 15)
-      const int cv = pos16 ^ (4 * row4);                           // V: chunk c sits at position c ^ 4 (r & 3)
+      const int ck = pos16 ^ row;
+      const int cv = pos16 ^ (4 * row4);
       lds_dma16(k_cache + grow + ck * 8, kdst + i * 4 * kHeadDim);
       lds_dma16(v_cache + grow + cv * 8, vdst + i * 4 * kHeadDim);
     }
   };
-  // Warm the L2 for the tile after the next one: the wave's KV block is 4 KiB of K and 4 KiB of V = 64 lines of
-  // 128 bytes, one per lane, fetched as 4-byte global-to-LDS loads into a scrap area that nobody reads.
+  // Warm the L2 for the tile after the next one: the wave's KV block is 4 KiB of K and 4 KiB of V, 64 half lines of
+  // 64 bytes each, one per lane, fetched as 4-byte global-to-LDS loads into a scrap area that nobody reads.
   auto touch = [&](int32_t block_id) {
     const size_t block_base = ((size_t)block_id * num_kv_heads + kvh) * kBlockSize * kHeadDim;
-    lds_dma4((lane < 32 ? k_cache : v_cache) + block_base + (lane & 31) * 64, scrap_lds + wave * 128);
+    lds_dma4_uniform(k_cache + block_base, lane * 64, scrap_lds + wave * 256);
+    lds_dma4_uniform(v_cache + block_base, lane * 64, scrap_lds + wave * 256 + 128);
   };
-  // This wave's tile loads have landed in LDS (the touch issued after them may still be under way), then every
-  // wave's have, and every wave is done with the other buffer.
+  // This wave's tile loads have landed in LDS (the two touches issued after them may still be under way), then
+  // every wave's have, and every wave is done with the other buffer.
   auto tiles_ready = [&]() {
-    asm volatile("s_waitcnt vmcnt(1)" ::: "memory");
+    asm volatile("s_waitcnt vmcnt(2)" ::: "memory");
     __syncthreads();
   };
   auto first_tile_ready = [&]() {                                  // nothing was issued after the tile's loads
@@ -338,7 +369,7 @@ __global__ __launch_bounds__(kPfThreads, 2) void prefill_chunk_kernel(
   __syncthreads();                                                 // every wave holds its q before tile 1 lands there
   for (int kt = 0; kt < n_tiles; ++kt) {
     if (kt + 1 < n_tiles) issue((kt + 1) * kPfKTile, (kt + 1) & 1, id1);
-    touch(id2);                                                    // unconditional: exactly one load follows the tile's
+    touch(id2);                                                    // unconditional: exactly two loads follow the tile's
     id1 = id2;
     id2 = lookup((kt + 3) * kPfKTile);
     compute(kt * kPfKTile, kt & 1);
