@@ -105,14 +105,6 @@ __device__ __forceinline__ void lds_dma16_x4(const uint16_t* base_uniform, uint3
       : "memory", "m0");
 }
 
-// The 4-byte form with a uniform base: lane l reads base + o and writes LDS bytes [dst + 4 l, dst + 4 l + 4).
-__device__ __forceinline__ void lds_dma4_uniform(const uint16_t* base_uniform, uint32_t o, uint16_t* dst_uniform) {
-  typedef __attribute__((address_space(3))) uint16_t lds_u16;
-  const uint32_t lds_addr = __builtin_amdgcn_readfirstlane((uint32_t)(uintptr_t)(lds_u16*)dst_uniform);
-  asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dword %1, %2" ::"s"(lds_addr), "v"(o), "s"(base_uniform)
-               : "memory", "m0");
-}
-
 template <typename T, int HW, bool kPosScale>
 __global__ __launch_bounds__(kPfThreads, 2) void prefill_chunk_kernel(
     const uint16_t* __restrict__ q, const int32_t* __restrict__ cu_q_lens, const uint16_t* __restrict__ k_cache,
@@ -122,7 +114,6 @@ __global__ __launch_bounds__(kPfThreads, 2) void prefill_chunk_kernel(
   constexpr int TT = 4 / HW;                       // 32-token tiles per workgroup
   constexpr int kTokensPerWg = kPfRows * TT;
   __shared__ __attribute__((aligned(1024))) uint16_t lds[4 * kTileElems64];    // K buffers 0, 1, then V buffers 0, 1
-  __shared__ __attribute__((aligned(256))) uint16_t scrap_lds[4 * 256];         // 512 bytes per wave, write-only
   uint16_t* const k_lds = lds;
   uint16_t* const v_lds = lds + 2 * kTileElems64;
 
@@ -154,6 +145,10 @@ __global__ __launch_bounds__(kPfThreads, 2) void prefill_chunk_kernel(
   const int q_end = cu_q_lens[r + 1];
   const int s_raw = seq_lens[r];
   const int32_t guessed_id = table[min(wave, max_blocks_per_seq - 1)];
+  // ... and the sequence's first 64 block ids, one per lane; later tiles read theirs out of this register, so the
+  // key loop holds no scalar memory loads (their returns would share a counter with the LDS reads of the products)
+  int32_t ids = table[min((int)(threadIdx.x & 63), max_blocks_per_seq - 1)];
+  int ids_chunk = 0;                                               // ids holds blocks 64 ids_chunk .. + 63
   asm volatile("" ::: "memory");                                   // keep the four loads together, ahead of their first use
   const int lq = q_end - q_begin;
   if (qt * kTokensPerWg >= lq) return;                             // uniform over the workgroup
@@ -199,12 +194,19 @@ __global__ __launch_bounds__(kPfThreads, 2) void prefill_chunk_kernel(
 
   // Tile loads.  Wave w brings KV block (k0/16 + w) into rows 16w .. 16w+15 of the K and V buffers: load i
   // of a wave fills rows 16w + 4i .. +3, lane l row 4i + l/16 of the block, chunk position l%16.  The block id
-  // is wave-uniform and is looked up one tile ahead of the loads that need it.  A key the workgroup cannot see
-  // is replaced by the last key it can see, whose rows are real, finite and already in cache; its weight is
-  // zero through the causal mask.
+  // is wave-uniform and is read out of the id register one tile ahead of the loads that need it.  A key the
+  // workgroup cannot see is replaced by the last key it can see, whose rows are real, finite and already in
+  // cache; its weight is zero through the causal mask.
   const int kv_last = max(wg_kv_end - 1, 0);
   const int last_block = kv_last / kBlockSize;
-  auto lookup = [&](int k0) { return table[min(k0 / kBlockSize + wave, last_block)]; };
+  auto lookup = [&](int k0) {
+    const int b = min(k0 / kBlockSize + wave, last_block);
+    if ((b >> 6) != ids_chunk) {                                   // uniform; once per 1024 keys
+      ids_chunk = b >> 6;
+      ids = table[min(ids_chunk * 64 + (int)(threadIdx.x & 63), last_block)];
+    }
+    return __builtin_amdgcn_readlane(ids, b & 63);
+  };
   const int pos16 = lane & 15;                                     // chunk position inside the LDS row
   const int row4 = lane >> 4;
   // per-lane byte offsets inside a (block, head) tile for the four loads of a block (see lds_dma16_x4); they do not
@@ -233,20 +235,8 @@ __global__ __launch_bounds__(kPfThreads, 2) void prefill_chunk_kernel(
       lds_dma16(v_cache + grow + cv * 8, vdst + i * 4 * kHeadDim);
     }
   };
-  // Warm the L2 for the tile after the next one: the wave's KV block is 4 KiB of K and 4 KiB of V, 64 half lines of
-  // 64 bytes each, one per lane, fetched as 4-byte global-to-LDS loads into a scrap area that nobody reads.
-  auto touch = [&](int32_t block_id) {
-    const size_t block_base = ((size_t)block_id * num_kv_heads + kvh) * kBlockSize * kHeadDim;
-    lds_dma4_uniform(k_cache + block_base, lane * 64, scrap_lds + wave * 256);
-    lds_dma4_uniform(v_cache + block_base, lane * 64, scrap_lds + wave * 256 + 128);
-  };
-  // This wave's tile loads have landed in LDS (the two touches issued after them may still be under way), then
-  // every wave's have, and every wave is done with the other buffer.
+  // This wave's tile loads have landed in LDS, then every wave's have, and every wave is done with the other buffer.
   auto tiles_ready = [&]() {
-    asm volatile("s_waitcnt vmcnt(2)" ::: "memory");
-    __syncthreads();
-  };
-  auto first_tile_ready = [&]() {                                  // nothing was issued after the tile's loads
     asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
     __syncthreads();
   };
@@ -361,17 +351,19 @@ __global__ __launch_bounds__(kPfThreads, 2) void prefill_chunk_kernel(
   // One barrier per tile: behind it every wave's part of tile kt+1 is in LDS and nobody reads tile kt any more.
   const int n_tiles = (wg_kv_end + kPfKTile - 1) / kPfKTile;
   issue(0, 0, wave <= last_block ? guessed_id : table[last_block]);
-  int32_t id1 = lookup(kPfKTile), id2 = lookup(2 * kPfKTile);       // block ids of the next two tiles
-  first_tile_ready();
+  int32_t id1 = table[min(kPfKTile / kBlockSize + wave, last_block)];   // block id of the next tile (scalar load: the
+                                                                        // id register is first needed in the loop)
+  tiles_ready();
 #pragma unroll
   for (int ks = 0; ks < 8; ++ks)
     qf[ks] = *reinterpret_cast<const u32x4*>(&q_park[col * kHeadDim + ((kswz ^ (2 * ks)) * 8)]);
   __syncthreads();                                                 // every wave holds its q before tile 1 lands there
   for (int kt = 0; kt < n_tiles; ++kt) {
+    // (the lookup comes first: should it have to fetch the next 64 ids, no tile load is in flight behind which the
+    // wait for them would queue up)
+    const int32_t id2 = lookup((kt + 2) * kPfKTile);
     if (kt + 1 < n_tiles) issue((kt + 1) * kPfKTile, (kt + 1) & 1, id1);
-    touch(id2);                                                    // unconditional: exactly two loads follow the tile's
     id1 = id2;
-    id2 = lookup((kt + 3) * kPfKTile);
     compute(kt * kPfKTile, kt & 1);
     tiles_ready();
   }
