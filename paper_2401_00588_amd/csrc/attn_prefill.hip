@@ -95,6 +95,12 @@ __device__ __forceinline__ void lds_dma16_x4(const uint16_t* base_uniform, uint3
                                              uint32_t o3, uint16_t* dst_uniform) {
   typedef __attribute__((address_space(3))) uint16_t lds_u16;
   const uint32_t lds_addr = __builtin_amdgcn_readfirstlane((uint32_t)(uintptr_t)(lds_u16*)dst_uniform);
+  // Pin the base to scalar registers also where the compiler would rather form the address with vector arithmetic
+  // (an "s" operand does not force that by itself).  The builtin returns int: widen through uint32_t.
+  const uint64_t base_bits = (uint64_t)(uintptr_t)base_uniform;
+  base_uniform = (const uint16_t*)(uintptr_t)(
+      (uint64_t)(uint32_t)__builtin_amdgcn_readfirstlane((int)(uint32_t)base_bits) |
+      ((uint64_t)(uint32_t)__builtin_amdgcn_readfirstlane((int)(uint32_t)(base_bits >> 32)) << 32));
   asm volatile(
       "s_mov_b32 m0, %0\n\ts_nop 0\n\t"
       "global_load_lds_dwordx4 %1, %5\n\t"
