@@ -196,3 +196,87 @@ def test_step_decode_replays_from_a_hip_graph(torch):
         for _ in range(charges):
             want_c = counter_update(want_c, ids.tolist(), None, n_out.tolist(), 1, 2)
         assert counters.cpu().tolist() == want_c
+
+
+def test_whole_mixed_step_replays_from_a_hip_graph(torch):
+    # One serving iteration -- append this step's K/V rows, prefill the new prompts' chunk, decode the running
+    # requests and charge the counters -- captured once and replayed on fresh inputs written into the same
+    # buffers: every call of the path is capturable and every replay redoes all of it.
+    say("append + prefill chunk + decode step captured into one graph")
+    rng = np.random.default_rng(951)
+    hq, hkv, dtype, clients = 8, 2, "bf16", 3
+    n_dec = 3
+    seq_after = np.array([40, 257, 16, 200, 90], dtype=np.int32)     # three decoding requests, two prompts
+    n_new = np.array([1, 1, 1, 72, 90], dtype=np.int32)              # a later chunk and a whole prompt
+    table, nb = make_block_table(rng, seq_after, 16)
+    cu_new = np.concatenate([[0], np.cumsum(n_new)]).astype(np.int32)
+    cu_pf = (cu_new[n_dec:] - cu_new[n_dec]).astype(np.int32)
+    p = vtc.make_params(hq, hkv, 128, 16, table.shape[1], dtype, SCALE)
+    ids = np.array([0, 2, 1, 1, 0], dtype=np.int32)
+    n_in = np.array([0, 0, 0, 72, 90], dtype=np.int32)
+    n_out = np.array([1, 1, 1, 0, 0], dtype=np.int32)
+
+    def fresh_inputs():
+        _, k_full, v_full = make_qkv_numpy(rng, 1, hq, hkv, 128, nb, 16, dtype)
+        q_dec = make_qkv_numpy(rng, n_dec, hq, hkv, 128, 1, 16, dtype)[0]
+        q_pf = make_qkv_numpy(rng, int(cu_pf[-1]), hq, hkv, 128, 1, 16, dtype)[0]
+        k_hole, v_hole = k_full.copy(), v_full.copy()
+        new_k, new_v = [], []
+        for r, (s, n) in enumerate(zip(seq_after, n_new)):
+            for pos in range(s - n, s):
+                blk, row = table[r, pos // 16], pos % 16
+                new_k.append(k_full[blk, :, row, :].copy())
+                new_v.append(v_full[blk, :, row, :].copy())
+                k_hole[blk, :, row, :] = 0x7FC0                      # NaN where this step's rows go
+                v_hole[blk, :, row, :] = 0x7FC0
+        return q_dec, q_pf, k_full, v_full, k_hole, v_hole, np.stack(new_k), np.stack(new_v)
+
+    first = fresh_inputs()
+    qd, qp = bits_to_tensor(first[0], dtype), bits_to_tensor(first[1], dtype)
+    kc, vc = bits_to_tensor(first[4], dtype), bits_to_tensor(first[5], dtype)
+    nk, nv = bits_to_tensor(first[6], dtype), bits_to_tensor(first[7], dtype)
+    t_all, s_all, cu_d = _i32(torch, table), _i32(torch, seq_after), _i32(torch, cu_new)
+    t_dec, s_dec = _i32(torch, table[:n_dec]), _i32(torch, seq_after[:n_dec])
+    t_pf, s_pf, cu_pf_d = _i32(torch, table[n_dec:]), _i32(torch, seq_after[n_dec:]), _i32(torch, cu_pf)
+    idd, nind, noutd = _i32(torch, ids), _i32(torch, n_in), _i32(torch, n_out)
+    counters = _i64(torch, np.zeros(clients, dtype=np.int64))
+    out_d, out_p = torch.empty_like(qd), torch.empty_like(qp)
+    ws = torch.empty(vtc.vtc_attn_workspace_bytes(p, n_dec, 0), dtype=torch.uint8, device="cuda")
+
+    def step():
+        vtc.vtc_kv_append(p, nk, nv, cu_d, int(n_new.max()), kc, vc, t_all, s_all)
+        vtc.vtc_attn_prefill_chunk(p, qp, cu_pf_d, int(n_new[n_dec:].max()), kc, vc, t_pf, s_pf, out=out_p)
+        vtc.vtc_step_decode(p, qd, kc, vc, t_dec, s_dec, counters, idd, nind, noutd, 1, 2, out=out_d, workspace=ws)
+
+    def check(inputs, charges):
+        q_dec, q_pf, k_full, v_full = inputs[:4]
+        assert np.array_equal(tensor_to_bits(kc), k_full) and np.array_equal(tensor_to_bits(vc), v_full)
+        want_d = OA.paged_decode(q_dec, k_full, v_full, table[:n_dec], seq_after[:n_dec], SCALE, dtype)
+        want_p = OA.paged_prefill_chunk(q_pf, cu_pf, k_full, v_full, table[n_dec:], seq_after[n_dec:], SCALE, dtype)
+        assert within_tolerance(OA.widen(tensor_to_bits(out_d), dtype), want_d, dtype)
+        assert within_tolerance(OA.widen(tensor_to_bits(out_p), dtype), want_p, dtype)
+        want_c = [0] * clients
+        for _ in range(charges):
+            want_c = counter_update(want_c, ids.tolist(), n_in.tolist(), n_out.tolist(), 1, 2)
+        assert counters.cpu().tolist() == want_c
+
+    step()                                   # eager once: first-call set-up happens outside the capture
+    torch.cuda.synchronize()
+    check(first, 1)
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        step()
+    torch.cuda.synchronize()
+    for replay in range(3):
+        inputs = fresh_inputs()              # new q, new cache contents, new rows to append: same buffers
+        qd.copy_(bits_to_tensor(inputs[0], dtype))
+        qp.copy_(bits_to_tensor(inputs[1], dtype))
+        kc.copy_(bits_to_tensor(inputs[4], dtype))
+        vc.copy_(bits_to_tensor(inputs[5], dtype))
+        nk.copy_(bits_to_tensor(inputs[6], dtype))
+        nv.copy_(bits_to_tensor(inputs[7], dtype))
+        out_d.fill_(float("nan"))
+        out_p.fill_(float("nan"))
+        graph.replay()
+        torch.cuda.synchronize()
+        check(inputs, replay + 2)
