@@ -682,13 +682,13 @@ __global__ __launch_bounds__(kWave, Engine::kMinWavesPerSimd) void decode_attend
 // Only a sequence-head that a range boundary cuts needs merging, so the merge is driven by the
 // boundaries: block w looks at the cut between waves w-1 and w.  If that cut falls inside a
 // (r, kv head) and wave w-1 holds its beginning, the block combines the pieces of waves
-// w-1, w, w+1, ... for one of the G query heads of that kv head (blockIdx.y).  Blocks past the
-// waves zero the output rows of empty sequences.
+// w-1, w, w+1, ... for the G query heads of that kv head, one wave of the workgroup per head
+// (threadIdx.y).  Blocks past the waves zero the output rows of empty sequences.
 constexpr int kFusedCounterTable = 512;          // clients whose sums a merge-launch workgroup keeps in LDS
 constexpr int kFusedCounterRequests = 1024;      // requests per such workgroup
 
-template <typename T>
-__global__ __launch_bounds__(kWave) void decode_merge_kernel(const DecodeHeader* __restrict__ header,
+template <typename T, int G>
+__global__ __launch_bounds__(kWave * G) void decode_merge_kernel(const DecodeHeader* __restrict__ header,
                                                              const int32_t* __restrict__ seq_lens,
                                                              const int4* __restrict__ wave_desc,
                                                              const float2* __restrict__ part_ml,
@@ -699,21 +699,21 @@ __global__ __launch_bounds__(kWave) void decode_merge_kernel(const DecodeHeader*
                                                              CounterJob job) {
   __shared__ u64 counter_table[kFusedCounterTable];
   const int lane = threadIdx.x;                          // dims 2*lane, 2*lane+1
-  const int group = num_q_heads / num_kv_heads;
-  const int g = blockIdx.y;                              // query head inside the group
+  constexpr int group = G;
+  const int g = threadIdx.y;                             // query head inside the group
+  const int tid = g * kWave + lane;
   if ((int)blockIdx.x >= max_waves + num_seqs) {         // the step's counter update
-    if (g != 0) return;
     const int begin = ((int)blockIdx.x - max_waves - num_seqs) * kFusedCounterRequests;
-    counter_reduce_slice<kWave, kFusedCounterTable>(counter_table, job.counters, job.num_clients, job.client_ids,
-                                                    begin, min(job.n, begin + kFusedCounterRequests),
-                                                    LinearTerm{job.n_in, job.n_out, job.w_p, job.w_q});
+    counter_reduce_slice<kWave * G, kFusedCounterTable>(counter_table, job.counters, job.num_clients, job.client_ids,
+                                                        begin, min(job.n, begin + kFusedCounterRequests),
+                                                        LinearTerm{job.n_in, job.n_out, job.w_p, job.w_q}, tid);
     return;
   }
   if ((int)blockIdx.x >= max_waves) {                    // empty sequences: all-zero rows
     const int r = blockIdx.x - max_waves;
-    if (g != 0 || min(seq_lens[r], max_tokens) > 0) return;
+    if (min(seq_lens[r], max_tokens) > 0) return;
     uint32_t* dst = reinterpret_cast<uint32_t*>(out + (size_t)r * num_q_heads * kHeadDim);
-    for (int i = lane; i < num_q_heads * (kHeadDim / 2); i += kWave) dst[i] = 0u;
+    for (int i = tid; i < num_q_heads * (kHeadDim / 2); i += kWave * G) dst[i] = 0u;
     return;
   }
   const int w = blockIdx.x;
@@ -787,7 +787,7 @@ static int launch_typed(const vtc_attn_params& p, int32_t num_seqs, const void* 
                      self_plan ? num_seqs : 0, header);
   if (ev_end && hipEventRecord(ev_end, stream) != hipSuccess) return VTC_ERR_HIP;
   const int counter_blocks = (job.n + kFusedCounterRequests - 1) / kFusedCounterRequests;
-  hipLaunchKernelGGL((decode_merge_kernel<T>), dim3(grid + num_seqs + counter_blocks, G), dim3(kWave), 0, stream,
+  hipLaunchKernelGGL((decode_merge_kernel<T, G>), dim3(grid + num_seqs + counter_blocks), dim3(kWave, G), 0, stream,
                      header, seq_lens, wave_desc, part_ml, part_acc, static_cast<uint16_t*>(out), num_seqs,
                      p.num_q_heads, p.num_kv_heads, grid, max_tokens, job);
   return hipGetLastError() == hipSuccess ? VTC_OK : VTC_ERR_HIP;

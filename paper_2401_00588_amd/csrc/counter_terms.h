@@ -65,16 +65,17 @@ struct PredictedTerm {                         // Algorithm 3, "adjust the cost 
 // (LDS atomics), then one 64-bit global atomic per client that received something.  Client tables
 // larger than kTable go to global atomics per request.  Unsigned 64-bit arithmetic, i.e. exact
 // two's-complement wrap-around; integer addition is associative, so any order gives the same counters.
+// `tid` is the thread's index among the kThreads of the workgroup (which need not be one-dimensional).
 template <int kThreads, int kTable, typename Term>
 __device__ __forceinline__ void counter_reduce_slice(u64* __restrict__ table, u64* __restrict__ counters,
                                                      int32_t num_clients, const int32_t* __restrict__ client_ids,
-                                                     int begin, int end, const Term& term) {
+                                                     int begin, int end, const Term& term, int tid) {
   const bool use_lds = num_clients <= kTable;
   if (use_lds) {
-    for (int i = threadIdx.x; i < num_clients; i += kThreads) table[i] = 0ull;
+    for (int i = tid; i < num_clients; i += kThreads) table[i] = 0ull;
     __syncthreads();
   }
-  for (int r = begin + (int)threadIdx.x; r < end; r += kThreads) {
+  for (int r = begin + tid; r < end; r += kThreads) {
     const int32_t c = client_ids[r];
     if (c < 0 || c >= num_clients) continue;
     const u64 delta = term(r, c);
@@ -86,7 +87,7 @@ __device__ __forceinline__ void counter_reduce_slice(u64* __restrict__ table, u6
   }
   if (use_lds) {
     __syncthreads();
-    for (int i = threadIdx.x; i < num_clients; i += kThreads) {
+    for (int i = tid; i < num_clients; i += kThreads) {
       const u64 d = table[i];
       if (d != 0ull) atomicAdd(&counters[i], d);
     }

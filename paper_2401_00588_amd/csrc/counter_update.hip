@@ -30,7 +30,7 @@ __global__ __launch_bounds__(kCounterThreads) void counter_reduce_kernel(u64* __
   __shared__ u64 table[kLdsClients];
   const int begin = blockIdx.x * kRequestsPerWorkgroup;
   counter_reduce_slice<kCounterThreads, kLdsClients>(table, counters, num_clients, client_ids, begin,
-                                                     min(n, begin + kRequestsPerWorkgroup), term);
+                                                     min(n, begin + kRequestsPerWorkgroup), term, threadIdx.x);
 }
 
 template <typename Term>
