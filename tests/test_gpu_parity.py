@@ -138,6 +138,22 @@ def test_decode_ignores_rows_past_seq_len_and_handles_empty_sequences(torch, dty
     assert (got[0] == 0).all() and (got[4] == 0).all()
 
 
+@pytest.mark.parametrize("n", [1, 5, 1500])
+def test_decode_of_a_batch_with_no_tokens_at_all(torch, n):
+    # every sequence empty: nothing to read, every output row is zero (both planning paths)
+    say(f"decode of {n} empty sequences")
+    rng = np.random.default_rng(40 + n)
+    table, nb = make_block_table(rng, [0] * n, 16, min_row_len=3)
+    q, k, v = make_qkv_numpy(rng, n, 8, 2, 128, nb, 16, "bf16")
+    p = vtc.make_params(8, 2, 128, 16, table.shape[1], "bf16", SCALE)
+    out = torch.full((n, 8, 128), float("nan"), dtype=torch.bfloat16, device="cuda")
+    vtc.vtc_attn_decode(p, bits_to_tensor(q, "bf16"), bits_to_tensor(k, "bf16"), bits_to_tensor(v, "bf16"),
+                        _i32(torch, table), _i32(torch, [0] * n), out=out)
+    torch.cuda.synchronize()
+    assert (tensor_to_bits(out) == 0).all()
+    assert (OA.paged_decode(q, k, v, table, [0] * n, SCALE, "bf16") == 0).all()
+
+
 @pytest.mark.parametrize("n,hq,hkv,dtype", [(2500, 4, 2, "bf16"), (9000, 2, 2, "f16")])
 def test_decode_many_short_sequences(torch, n, hq, hkv, dtype):
     # more sequences than one planning pass (1024) and than the planner's on-chip prefix table (8192) hold;
