@@ -87,6 +87,14 @@ __device__ __forceinline__ void lds_dma16(const uint16_t* src, uint16_t* dst_uni
   asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, off" ::"s"(lds_addr), "v"(src) : "memory", "m0");
 }
 
+// The same for data that is read once (the q rows): marked non-temporal so that it does not displace the K/V
+// tiles, which several workgroups share, from the L2.
+__device__ __forceinline__ void lds_dma16_once(const uint16_t* src, uint16_t* dst_uniform) {
+  typedef __attribute__((address_space(3))) uint16_t lds_u16;
+  const uint32_t lds_addr = __builtin_amdgcn_readfirstlane((uint32_t)(uintptr_t)(lds_u16*)dst_uniform);
+  asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, off nt" ::"s"(lds_addr), "v"(src) : "memory", "m0");
+}
+
 // The same with a wave-uniform base address and 32-bit per-lane byte offsets, four loads at once: load i reads
 // base + o_i + 1024 i and writes LDS bytes [dst + 1024 i + 16 l, + 16) (the instruction's immediate offset moves
 // both addresses).  One KV block's K or V rows (4 KiB) are four such 1 KiB slices; the addresses cost no vector
@@ -187,7 +195,7 @@ __global__ __launch_bounds__(kPfThreads, 2) void prefill_chunk_kernel(
   for (int i = 0; i < 8; ++i) {
     const int j = 4 * i + (lane >> 4);                                                   // row of the wave's 32
     const uint16_t* src = q + ((size_t)(q_begin + min(tok0 + j, lq - 1)) * num_q_heads + h) * kHeadDim;
-    lds_dma16(src + (((lane & 15) ^ (j & 15)) * 8), q_park + i * 4 * kHeadDim);
+    lds_dma16_once(src + (((lane & 15) ^ (j & 15)) * 8), q_park + i * 4 * kHeadDim);
   }
 
   f32x16 oacc[4];
@@ -398,7 +406,8 @@ __global__ __launch_bounds__(kPfThreads, 2) void prefill_chunk_kernel(
       const int row = 4 * i + (lane >> 4);
       const u32x4 v = *reinterpret_cast<const u32x4*>(&patch[row * kPitchO + (lane & 15) * 8]);
       if (tok0 + row < lq)
-        *reinterpret_cast<u32x4*>(out + ((size_t)(q_begin + tok0 + row) * num_q_heads + h) * kHeadDim + (lane & 15) * 8) = v;
+        // (written once and not read again here: non-temporal, so that it does not displace K/V tiles from the L2)
+        __builtin_nontemporal_store(v, reinterpret_cast<u32x4*>(out + ((size_t)(q_begin + tok0 + row) * num_q_heads + h) * kHeadDim + (lane & 15) * 8));
     }
   }
 }
