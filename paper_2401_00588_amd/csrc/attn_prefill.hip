@@ -50,6 +50,7 @@ constexpr int kQkAhead = VTC_PREFILL_QK_AHEAD;   // K fragments in flight ahead 
 #endif
 constexpr int kPvAhead = VTC_PREFILL_PV_AHEAD;   // V^T fragments in flight ahead of the product that uses them
 constexpr int kXcds = 8;                 // accelerator complex dies of an MI355X
+constexpr int kCusPerXcd = 32;           // compute units on each of them
 constexpr int kPfThreads = 256;
 constexpr int kPfRows = 32;              // query rows per wave
 constexpr int kPfKTile = 64;             // keys per LDS tile
@@ -141,8 +142,17 @@ __global__ __launch_bounds__(kPfThreads, 2) void prefill_chunk_kernel(
   if (n_units % kXcds == 0) {
     const int per_xcd = n_units / kXcds;
     const int j = linear / kXcds;
-    unit = (j % per_xcd) * kXcds + linear % kXcds;
-    qt = j / per_xcd;
+    // Units go in groups whose query tiles come to about one workgroup per CU of the XCD, and inside a group the
+    // order is query tile first, unit second: the XCD's 4 MB L2 then serves the K/V of a few units at a time, each
+    // of them to all its query tiles at once, instead of a slice of every unit's K/V in every round of workgroups.
+    // (Measured on 16 units x 8 query tiles per XCD: groups of 4 units -7 % on a 256-key chunk, -1.5 % on a
+    // 512-key chunk against no grouping; groups of 1, 2, 3 or 8 units are slower than 4.)
+    const int gsz = min(per_xcd, max(1, kCusPerXcd / n_qt));
+    const int per_group = gsz * n_qt;
+    const int grp = j / per_group, jj = j % per_group;
+    const int in_grp = min(gsz, per_xcd - grp * gsz);             // the last group may be smaller
+    unit = (grp * gsz + jj % in_grp) * kXcds + linear % kXcds;
+    qt = jj / in_grp;
   } else {                                                         // odd shapes: plain order
     qt = blockIdx.x;
     unit = blockIdx.y + gridDim.y * blockIdx.z;
