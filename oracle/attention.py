@@ -16,6 +16,10 @@ The reading used here is standard scaled dot-product attention:
   p = seq_len - Lq + i and sees keys 0..p inclusive.
 * Query head h reads KV head h // (Hq // Hkv).
 * seq_len == 0 gives an all-zero output row.
+* A prefill chunk that is longer than the context it is said to end
+  (seq_len < Lq) has no positions to give its tokens: all its output rows are
+  zero and none of its cache blocks is looked at (the library's stated
+  behaviour for that caller slip; the paper has nothing to say about it).
 
 Everything is three plain passes in float64; no online update, no blocking.
 Stored 16-bit values are widened exactly.  TEST INFRASTRUCTURE ONLY.
@@ -127,6 +131,9 @@ def paged_prefill_chunk(
         g = h // group
         s = int(seq_lens[r])
         lq = int(cu_q_lens[r + 1]) - int(cu_q_lens[r])
+        if s < lq:                           # inconsistent sequence: zero rows, cache untouched
+            out[int(cu_q_lens[r]) + i, h] = 0.0
+            continue
         if (r, g) not in cached:
             cached.clear()
             cached[(r, g)] = (

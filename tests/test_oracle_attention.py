@@ -108,6 +108,28 @@ def test_empty_context_gives_zeros():
     assert np.abs(out[0]).sum() > 0 and np.abs(out[2]).sum() > 0
 
 
+def test_a_chunk_longer_than_its_context_gives_zero_rows_and_reads_no_block():
+    # seq_len < chunk length is a caller slip: the rows of that sequence are zero, its block-table row (here
+    # ids far outside the cache) is never followed, and the sequences around it are computed as usual
+    rng = np.random.default_rng(6)
+    hq, hkv, d, bs = 4, 2, 8, 4
+    seq_lens = [9, 3, 0, 7]
+    q_lens = [4, 5, 2, 7]
+    keys = [rng.standard_normal((s, hkv, d), dtype=np.float32) for s in seq_lens]
+    vals = [rng.standard_normal((s, hkv, d), dtype=np.float32) for s in seq_lens]
+    kc, vc, table, sl = pack_paged(keys, vals, bs, "bf16", rng)
+    cu = np.concatenate([[0], np.cumsum(q_lens)])
+    q = f32_to_storage_bits(rng.standard_normal((int(cu[-1]), hq, d), dtype=np.float32), "bf16")
+    poisoned = table.copy()
+    poisoned[1, :] = 10 ** 6
+    poisoned[2, :] = -7
+    out = A.paged_prefill_chunk(q, cu, kc, vc, poisoned, sl, 0.3, "bf16")
+    assert np.array_equal(out[cu[1]:cu[3]], np.zeros((7, hq, d)))
+    good = A.paged_prefill_chunk(q, cu, kc, vc, table, [9, 5, 2, 7], 0.3, "bf16", rows=[(0, 3, 1), (3, 6, 2)])
+    assert np.array_equal(out[cu[0] + 3, 1], good[cu[0] + 3, 1]) and np.array_equal(out[cu[3] + 6, 2], good[cu[3] + 6, 2])
+    assert np.abs(out[cu[0] + 3, 1]).sum() > 0
+
+
 # ---------------------------------------------------------------- invariances
 def test_key_permutation_invariance():
     rng = np.random.default_rng(6)
