@@ -30,8 +30,10 @@
  *     Device-resident contents (seq_lens, block_table, client_ids, ...) are
  *     trusted, except where a clamp is documented.
  *
- * Layouts (row-major, last index fastest; E = 2-byte element, fp16 or bf16)
- *   q, out        E [num_q_tokens, num_q_heads, head_dim]
+ * Layouts (row-major, last index fastest; E = 2-byte element, fp16 or bf16;
+ * O = the element type named by out_dtype: E, or 4-byte float)
+ *   q             E [num_q_tokens, num_q_heads, head_dim]
+ *   out           O [num_q_tokens, num_q_heads, head_dim]
  *   k_cache,
  *   v_cache       E [num_blocks, num_kv_heads, block_size, head_dim]
  *   block_table   int32 [num_seqs, max_blocks_per_seq]   physical block ids
@@ -49,12 +51,13 @@
 extern "C" {
 #endif
 
-typedef enum { VTC_F16 = 0, VTC_BF16 = 1 } vtc_dtype;
+typedef enum { VTC_F16 = 0, VTC_BF16 = 1, VTC_F32 = 2 /* output rows only */ } vtc_dtype;
 
 enum {
   VTC_OK = 0,
   VTC_ERR_INVALID_ARG = -1,         /* null pointer, negative size, inconsistent sizes   */
   VTC_ERR_UNSUPPORTED = -2,         /* head_dim != 128, block_size != 16, unknown dtype,
+                                       out_dtype neither dtype nor VTC_F32,
                                        num_q_heads/num_kv_heads not in {1,2,4,8}          */
   VTC_ERR_WORKSPACE_TOO_SMALL = -3, /* workspace_bytes < vtc_attn_workspace_bytes(...)   */
   VTC_ERR_HIP = -4                  /* a HIP runtime call or kernel launch failed        */
@@ -67,16 +70,24 @@ typedef struct {
   int32_t head_dim;           /* 128                                             */
   int32_t block_size;         /* tokens per KV block: 16                         */
   int32_t max_blocks_per_seq; /* row stride of block_table                       */
-  int32_t dtype;              /* vtc_dtype of q, k_cache, v_cache and out        */
+  int32_t dtype;              /* vtc_dtype of q, k_cache and v_cache: F16 or BF16 */
   float scale;                /* logit scale, normally 1/sqrt(head_dim)          */
+  int32_t out_dtype;          /* vtc_dtype of out: equal to dtype (the fp32 result
+                                 is rounded to nearest even), or VTC_F32 (the fp32
+                                 result as it stands, no final rounding)          */
 } vtc_attn_params;
 
 /*
- * Bytes of device workspace that vtc_attn_decode needs for up to max_num_seqs
- * sequences of up to max_seq_len context tokens each (max_seq_len <= 0, or
- * larger than the block table can address, means max_blocks_per_seq *
- * block_size).  Pure host arithmetic.  Returns 0 if params is NULL or
- * unsupported.  vtc_attn_prefill_chunk needs no workspace.
+ * Bytes of device workspace with which vtc_attn_decode can put every wave to use
+ * that the current device holds at once, for up to max_num_seqs sequences of up
+ * to max_seq_len context tokens each (max_seq_len <= 0, or larger than the block
+ * table can address, means max_blocks_per_seq * block_size).  The footprint is a
+ * fixed part plus a share per wave (two fp32 partial results per query head of a
+ * group), and short batches cannot use many waves, so it grows with
+ * max_num_seqs * max_seq_len until the device's wave count caps it (a few MB to
+ * a few tens of MB).  Host arithmetic plus one query of the current device's
+ * compute-unit count (256 is assumed when there is no usable device).  Returns 0
+ * if params is NULL or unsupported.  vtc_attn_prefill_chunk needs no workspace.
  */
 size_t vtc_attn_workspace_bytes(const vtc_attn_params* params /*[host]*/, int32_t max_num_seqs,
                                 int32_t max_seq_len);
@@ -89,7 +100,7 @@ size_t vtc_attn_workspace_bytes(const vtc_attn_params* params /*[host]*/, int32_
  *     out[r,h,:] = sum_j softmax_j(scale * <q[r,h,:], K_j>) * V_j,  j in [0, seq_lens[r])
  * over the cached tokens of KV head h / (Hq/Hkv).  The K/V of the current
  * token must already be in the cache (seq_lens includes it).  Accumulation is
- * fp32; out is rounded to the storage dtype (nearest even).  seq_lens[r] == 0
+ * fp32; out is rounded to out_dtype (nearest even; no rounding for VTC_F32).  seq_lens[r] == 0
  * gives an all-zero row.  seq_lens[r] is clamped to max_blocks_per_seq *
  * block_size.  Rows of the last block past seq_lens[r], and block_table
  * entries past the last block, are never used (they may hold anything).
@@ -98,13 +109,20 @@ size_t vtc_attn_workspace_bytes(const vtc_attn_params* params /*[host]*/, int32_
  *   k_cache, v_cache    [device] paged caches, read only
  *   block_table         [device] int32 [num_seqs, max_blocks_per_seq]
  *   seq_lens            [device] int32 [num_seqs]
- *   out [device]        E [num_seqs, Hq, 128], written
- *   workspace [device]  >= vtc_attn_workspace_bytes(params, num_seqs, 0) bytes,
- *                       256-byte aligned, contents undefined before and after
+ *   out [device]        O [num_seqs, Hq, 128], written
+ *   workspace [device]  256-byte aligned, contents undefined before and after.
+ *                       vtc_attn_workspace_bytes(params, num_seqs, L) bytes serve
+ *                       contexts of up to L tokens at full speed; the call uses as
+ *                       many waves as workspace_bytes has room for, so a smaller
+ *                       workspace gives the same results more slowly, and
+ *                       VTC_ERR_WORKSPACE_TOO_SMALL only if not even one wave fits
+ *                       (vtc_attn_workspace_bytes(params, num_seqs, 1) always does).
  * num_seqs == 0 is a successful no-op.  The call enqueues the attention kernel
  * and a merge kernel on hip_stream (batches of more than 1024 sequences: a
  * planning kernel first); two calls that share one workspace must be ordered on
- * the same stream.
+ * the same stream.  It allocates nothing, never synchronises and keeps no state
+ * between calls, so it may be captured into a HIP graph.  On VTC_ERR_HIP the
+ * contents of out are undefined.
  */
 int vtc_attn_decode(const vtc_attn_params* params /*[host]*/, int32_t num_seqs, const void* q,
                     const void* k_cache, const void* v_cache, const int32_t* block_table,
@@ -171,14 +189,20 @@ int vtc_step_decode_profiled(const vtc_attn_params* params /*[host]*/, int32_t n
  * chunk token i sits at absolute position p = seq_lens[r] - Lq_r + i and
  * attends to cached tokens 0..p inclusive:
  *     out[row,h,:] = sum_{j<=p} softmax_j(scale * <q[row,h,:], K_j>) * V_j
- * fp32 accumulation, output rounded to the storage dtype.  Softmax weights are
- * rounded to the storage dtype before the P*V product (matrix-core operand).
+ * fp32 accumulation, output rounded to out_dtype.  The softmax weights enter the
+ * P*V product as matrix-core operands of the storage type: fp16 weights with
+ * their 11 significant bits, bf16 weights as two operands (the rounded weight
+ * and what the rounding dropped), i.e. with 16 significant bits.
+ * A sequence whose seq_lens[r] (clamped to 0 .. max_blocks_per_seq * block_size)
+ * is smaller than Lq_r has no positions for its chunk tokens: all its output
+ * rows are zero and no cache block is read for it (its block_table row may hold
+ * anything).
  *
  *   q [device]          E [total_q_tokens, Hq, 128], total_q_tokens = cu_q_lens[num_seqs]
  *   cu_q_lens [device]  int32 [num_seqs + 1], non-decreasing, cu_q_lens[0] == 0
  *   max_q_len           host-side upper bound on every Lq_r (sizes the launch)
- *   seq_lens [device]   int32 [num_seqs], seq_lens[r] >= Lq_r
- *   out [device]        E [total_q_tokens, Hq, 128], written
+ *   seq_lens [device]   int32 [num_seqs], seq_lens[r] >= Lq_r (see above for the other case)
+ *   out [device]        O [total_q_tokens, Hq, 128], written
  *   workspace           unused, may be NULL
  * num_seqs == 0 or max_q_len == 0 is a successful no-op.
  */

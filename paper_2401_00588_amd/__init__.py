@@ -11,6 +11,7 @@ from .binding import (  # noqa: F401
     HipEvent,
     VTC_BF16,
     VTC_F16,
+    VTC_F32,
     VtcError,
     library_path,
     load_library,

@@ -12,6 +12,7 @@ from typing import Optional
 
 VTC_F16 = 0
 VTC_BF16 = 1
+VTC_F32 = 2          # output rows only
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
 _LIB_NAME = "libvtc_mi355x.so"
@@ -35,6 +36,7 @@ class AttnParams(ctypes.Structure):
         ("max_blocks_per_seq", ctypes.c_int32),
         ("dtype", ctypes.c_int32),
         ("scale", ctypes.c_float),
+        ("out_dtype", ctypes.c_int32),
     ]
 
 
@@ -101,18 +103,23 @@ def vtc_strerror(code: int) -> str:
     return load_library().vtc_strerror(int(code)).decode("ascii")
 
 
-def make_params(num_q_heads: int, num_kv_heads: int, head_dim: int, block_size: int,
-                max_blocks_per_seq: int, dtype, scale: float) -> AttnParams:
-    """``dtype`` is VTC_F16 / VTC_BF16, "f16" / "bf16", or a torch dtype."""
+def _dtype_code(dtype) -> int:
     if isinstance(dtype, str):
-        code = {"f16": VTC_F16, "bf16": VTC_BF16}[dtype]
-    elif isinstance(dtype, int):
-        code = dtype
-    else:
-        import torch
+        return {"f16": VTC_F16, "bf16": VTC_BF16, "f32": VTC_F32}[dtype]
+    if isinstance(dtype, int):
+        return dtype
+    import torch
 
-        code = {torch.float16: VTC_F16, torch.bfloat16: VTC_BF16}[dtype]
-    return AttnParams(num_q_heads, num_kv_heads, head_dim, block_size, max_blocks_per_seq, code, scale)
+    return {torch.float16: VTC_F16, torch.bfloat16: VTC_BF16, torch.float32: VTC_F32}[dtype]
+
+
+def make_params(num_q_heads: int, num_kv_heads: int, head_dim: int, block_size: int,
+                max_blocks_per_seq: int, dtype, scale: float, out_dtype=None) -> AttnParams:
+    """``dtype`` is VTC_F16 / VTC_BF16, "f16" / "bf16", or a torch dtype; ``out_dtype`` (default: the same)
+    may also be VTC_F32 / "f32" / torch.float32 for unrounded fp32 output rows."""
+    code = _dtype_code(dtype)
+    out_code = code if out_dtype is None else _dtype_code(out_dtype)
+    return AttnParams(num_q_heads, num_kv_heads, head_dim, block_size, max_blocks_per_seq, code, scale, out_code)
 
 
 def vtc_attn_workspace_bytes(params: AttnParams, max_num_seqs: int, max_seq_len: int = 0) -> int:
@@ -129,6 +136,10 @@ def _torch():
 def _elt_dtype(params: AttnParams):
     torch = _torch()
     return torch.float16 if params.dtype == VTC_F16 else torch.bfloat16
+
+
+def _out_dtype(params: AttnParams):
+    return _torch().float32 if params.out_dtype == VTC_F32 else _elt_dtype(params)
 
 
 def _check(t, name: str, dtype, ndim: Optional[int] = None) -> None:
@@ -211,8 +222,8 @@ def vtc_attn_decode(params: AttnParams, q, k_cache, v_cache, block_table, seq_le
     if tuple(block_table.shape) != (n, params.max_blocks_per_seq):
         raise ValueError("block_table must be [num_seqs, max_blocks_per_seq]")
     if out is None:
-        out = torch.empty_like(q)
-    _check(out, "out", elt, 3)
+        out = torch.empty_like(q, dtype=_out_dtype(params))
+    _check(out, "out", _out_dtype(params), 3)
     if out.shape != q.shape:
         raise ValueError("out must have the shape of q")
     need = vtc_attn_workspace_bytes(params, n, 0)
@@ -258,8 +269,8 @@ def vtc_step_decode(params: AttnParams, q, k_cache, v_cache, block_table, seq_le
     if tuple(block_table.shape) != (n, params.max_blocks_per_seq):
         raise ValueError("block_table must be [num_seqs, max_blocks_per_seq]")
     if out is None:
-        out = torch.empty_like(q)
-    _check(out, "out", elt, 3)
+        out = torch.empty_like(q, dtype=_out_dtype(params))
+    _check(out, "out", _out_dtype(params), 3)
     if out.shape != q.shape:
         raise ValueError("out must have the shape of q")
     _check(counters, "counters", torch.int64, 1)
@@ -311,8 +322,8 @@ def vtc_attn_prefill_chunk(params: AttnParams, q, cu_q_lens, max_q_len: int, k_c
     if tuple(block_table.shape) != (n, params.max_blocks_per_seq):
         raise ValueError("block_table must be [num_seqs, max_blocks_per_seq]")
     if out is None:
-        out = torch.empty_like(q)
-    _check(out, "out", elt, 3)
+        out = torch.empty_like(q, dtype=_out_dtype(params))
+    _check(out, "out", _out_dtype(params), 3)
     if out.shape != q.shape:
         raise ValueError("out must have the shape of q")
     rc = lib.vtc_attn_prefill_chunk(ctypes.byref(params), n, q.data_ptr(), cu_q_lens.data_ptr(), int(max_q_len),

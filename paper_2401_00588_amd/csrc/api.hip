@@ -41,7 +41,8 @@ const char* vtc_strerror(int code) {
 
 size_t vtc_attn_workspace_bytes(const vtc_attn_params* params, int32_t max_num_seqs, int32_t max_seq_len) {
   if (vtc::check_params(params) != VTC_OK || max_num_seqs < 0) return 0;
-  return vtc::decode_workspace_layout(*params, max_num_seqs, max_seq_len).total_bytes;
+  return vtc::decode_workspace_layout(*params, max_num_seqs, vtc::decode_waves_for(*params, max_num_seqs, max_seq_len))
+      .total_bytes;
 }
 
 static int decode_common(const vtc_attn_params* params, int32_t num_seqs, const void* q, const void* k_cache,
@@ -57,9 +58,10 @@ static int decode_common(const vtc_attn_params* params, int32_t num_seqs, const 
   if ((reinterpret_cast<uintptr_t>(q) & 15u) || (reinterpret_cast<uintptr_t>(out) & 15u) ||
       (reinterpret_cast<uintptr_t>(k_cache) & 15u) || (reinterpret_cast<uintptr_t>(v_cache) & 15u))
     return VTC_ERR_INVALID_ARG;
-  if (workspace_bytes < vtc::decode_workspace_layout(*params, num_seqs, 0).total_bytes)
-    return VTC_ERR_WORKSPACE_TOO_SMALL;
-  return vtc::launch_decode(*params, num_seqs, q, k_cache, v_cache, block_table, seq_lens, out, workspace,
+  // the launch uses as many waves as the workspace has room for (and the device can hold)
+  const int max_waves = vtc::decode_wave_capacity(*params, num_seqs, workspace_bytes, vtc::decode_wave_bound());
+  if (max_waves < 1) return VTC_ERR_WORKSPACE_TOO_SMALL;
+  return vtc::launch_decode(*params, num_seqs, q, k_cache, v_cache, block_table, seq_lens, out, workspace, max_waves,
                             static_cast<hipStream_t>(hip_stream), static_cast<hipEvent_t>(ev_begin),
                             static_cast<hipEvent_t>(ev_end), job);
 }

@@ -137,7 +137,7 @@ __global__ __launch_bounds__(kPlanThreads) void decode_plan_kernel(const int32_t
 // up only its own range start.  Returns (r, h, b, n_blocks); n_blocks = 0 for a wave without a range.
 // Wave 0 also writes the header that the merge kernel reads.
 constexpr int kSelfPlanPerLane = 16;
-constexpr int kSelfPlanMaxSeqs = VTC_DECODE_SELF_PLAN ? kWave * kSelfPlanPerLane : 0;
+constexpr int kSelfPlanMaxSeqs = kWave * kSelfPlanPerLane;
 
 __device__ __forceinline__ int4 self_plan(const int32_t* __restrict__ seq_lens, int num_seqs, int num_kv_heads,
                                           int max_tokens, int max_waves, int wave, int lane,
@@ -238,17 +238,14 @@ __device__ __forceinline__ void load_tile(u32x4 (&dst)[4], const uint16_t* __res
   const u32x4* src = reinterpret_cast<const u32x4*>(tile) + lane;
 #pragma unroll
   for (int i = 0; i < 4; ++i) {
-#if VTC_DECODE_NT_LOADS
     dst[i] = __builtin_nontemporal_load(src + i * stride16);  // streamed once: keep it out of the caches' way
-#else
-    dst[i] = src[i * stride16];
-#endif
   }
 }
 
 // Where a finished piece goes: the output row block of its (sequence, kv head) and its partial slot.
 struct PieceSink {
-  uint16_t* out_rows;   // out + (r * Hq + h * G) * 128: G consecutive rows of 128
+  void* out_rows;       // G consecutive output rows of 128 (of the storage type, or fp32 when out_f32)
+  bool out_f32;
   float* part_acc;      // part_acc + slot0 * 128, slot0 = (wave * 2 + end) * G: G consecutive partials
   float2* part_ml;      // part_ml + slot0
 };
@@ -258,7 +255,7 @@ template <typename T, int G>
 struct ValuEngine {
   static constexpr int kQRegs = G;       // one 16-byte q slice per query head
   static constexpr int kLdsElems = 0;
-  static constexpr int kMinWavesPerSimd = G == 1 ? 4 : (G == 2 ? 3 : (G == 4 ? 2 : 1));   // register budget
+  static constexpr int kMinWavesPerSimd = G == 1 ? 4 : (G == 2 ? 3 : (G == 4 ? 2 : 1));   // register budget (used with G = 1)
   int row, sub;
   float m[G];        // running max of the scaled logits (log2 domain), per 16-lane row
   float l[G];        // running sum of exp2(logit - m)
@@ -369,10 +366,16 @@ struct ValuEngine {
       for (int g = 0; g < G; ++g) {
         if (whole) {
           const float inv = 1.f / l[g];
-          u32x4 o;
+          if (sink.out_f32) {
+            float4* dst = reinterpret_cast<float4*>(static_cast<float*>(sink.out_rows) + g * kHeadDim + sub * 8);
+            dst[0] = make_float4(acc[g][0] * inv, acc[g][1] * inv, acc[g][2] * inv, acc[g][3] * inv);
+            dst[1] = make_float4(acc[g][4] * inv, acc[g][5] * inv, acc[g][6] * inv, acc[g][7] * inv);
+          } else {
+            u32x4 o;
 #pragma unroll
-          for (int w2 = 0; w2 < 4; ++w2) o[w2] = pack2<T>(acc[g][2 * w2] * inv, acc[g][2 * w2 + 1] * inv);
-          *reinterpret_cast<u32x4*>(sink.out_rows + g * kHeadDim + sub * 8) = o;
+            for (int w2 = 0; w2 < 4; ++w2) o[w2] = pack2<T>(acc[g][2 * w2] * inv, acc[g][2 * w2 + 1] * inv);
+            *reinterpret_cast<u32x4*>(static_cast<uint16_t*>(sink.out_rows) + g * kHeadDim + sub * 8) = o;
+          }
         } else {
           float4* dst = reinterpret_cast<float4*>(sink.part_acc + g * kPartialFloats + sub * 8);
           dst[0] = make_float4(acc[g][0], acc[g][1], acc[g][2], acc[g][3]);
@@ -403,7 +406,7 @@ struct MfmaEngine {
   static constexpr int kPitchV = kHeadDim + 16;   // 288 B rows: the 16-row x 32-byte transposing reads use every bank twice
   static constexpr int kPitchQ = kHeadDim + 8;
   static constexpr int kLdsElems = kBlockSize * (kPitchK + kPitchV) + 4 * kQRegs * kPitchQ;
-  static constexpr int kMinWavesPerSimd = VTC_DECODE_MFMA_WAVES_PER_SIMD;   // register budget = 512 / this
+  static constexpr int kMinWavesPerSimd = 2;      // register budget = 512 / this (three waves spill)
   using f32x4 = float __attribute__((ext_vector_type(4)));
   using f16x8 = _Float16 __attribute__((ext_vector_type(8)));
   using bf16x8 = __bf16 __attribute__((ext_vector_type(8)));
@@ -499,7 +502,7 @@ struct MfmaEngine {
     const u32x2 pb = u32x2{pack2<T>(p[0], p[1]), pack2<T>(p[2], p[3])};   // P^T: tokens 4*kg + 0..3 of head j
     // bf16 keeps 8 bits of a weight.  What the rounding dropped goes through the second product as an
     // operand of its own, so the weights act with 16 bits (fp16's 11 bits are left as they are).
-    constexpr bool kSplitP = __is_same(T, BF16) && VTC_DECODE_BF16_SPLIT_P;
+    constexpr bool kSplitP = __is_same(T, BF16);
     u32x2 pr = u32x2{0u, 0u};
     if constexpr (kSplitP) {
       pr = u32x2{pack2<T>(p[0] - __builtin_bit_cast(float, pb[0] << 16),
@@ -528,11 +531,19 @@ struct MfmaEngine {
     if (j < G) {
       if (whole) {
         const float inv = 1.f / l_tot;
-        uint16_t* dst = sink.out_rows + j * kHeadDim + 4 * kg;
+        if (sink.out_f32) {
+          float* dst = static_cast<float*>(sink.out_rows) + j * kHeadDim + 4 * kg;
 #pragma unroll
-        for (int db = 0; db < 8; ++db) {
-          const u32x2 o = u32x2{pack2<T>(acc[db][0] * inv, acc[db][1] * inv), pack2<T>(acc[db][2] * inv, acc[db][3] * inv)};
-          *reinterpret_cast<u32x2*>(dst + db * 16) = o;
+          for (int db = 0; db < 8; ++db)
+            *reinterpret_cast<float4*>(dst + db * 16) =
+                make_float4(acc[db][0] * inv, acc[db][1] * inv, acc[db][2] * inv, acc[db][3] * inv);
+        } else {
+          uint16_t* dst = static_cast<uint16_t*>(sink.out_rows) + j * kHeadDim + 4 * kg;
+#pragma unroll
+          for (int db = 0; db < 8; ++db) {
+            const u32x2 o = u32x2{pack2<T>(acc[db][0] * inv, acc[db][1] * inv), pack2<T>(acc[db][2] * inv, acc[db][3] * inv)};
+            *reinterpret_cast<u32x2*>(dst + db * 16) = o;
+          }
         }
       } else {
         float* dst = sink.part_acc + j * kPartialFloats + 4 * kg;
@@ -557,8 +568,8 @@ struct StreamPos {
 template <typename T, int G, typename Engine>
 __global__ __launch_bounds__(kWave, Engine::kMinWavesPerSimd) void decode_attend_kernel(
     const uint16_t* __restrict__ q, const uint16_t* __restrict__ k_cache, const uint16_t* __restrict__ v_cache,
-    const int32_t* __restrict__ block_table, const int32_t* __restrict__ seq_lens, uint16_t* __restrict__ out,
-    int4* __restrict__ wave_desc, float2* __restrict__ part_ml, float* __restrict__ part_acc,
+    const int32_t* __restrict__ block_table, const int32_t* __restrict__ seq_lens, void* __restrict__ out,
+    int32_t out_f32, int4* __restrict__ wave_desc, float2* __restrict__ part_ml, float* __restrict__ part_acc,
     int32_t num_kv_heads, int32_t max_blocks_per_seq, float scale2, int32_t self_plan_seqs,
     DecodeHeader* __restrict__ header) {
   constexpr int kQRegs = Engine::kQRegs;
@@ -569,7 +580,7 @@ __global__ __launch_bounds__(kWave, Engine::kMinWavesPerSimd) void decode_attend
   const int wave = blockIdx.x;
   int4 desc_v;
   if (self_plan_seqs > 0) {                // no planning launch: derive the range here, leave it for the merge
-    __shared__ int32_t lens_lds[kSelfPlanMaxSeqs > 0 ? kSelfPlanMaxSeqs : 1];
+    __shared__ int32_t lens_lds[kSelfPlanMaxSeqs];
     desc_v = self_plan(seq_lens, self_plan_seqs, num_kv_heads, max_tokens, gridDim.x, wave, lane, header, lens_lds);
     if (lane == 0) wave_desc[wave] = desc_v;
   } else {
@@ -639,7 +650,8 @@ __global__ __launch_bounds__(kWave, Engine::kMinWavesPerSimd) void decode_attend
     const bool whole = piece_lo == 0 && last_of_seq;     // the piece is the entire sequence
     // partial slot 0: the piece cut at the start of this wave's range; slot 1: the one cut at its end
     const size_t slot0 = ((size_t)wave * 2 + (piece_lo == 0 ? 1 : 0)) * G;
-    eng.finish(whole, PieceSink{out + ((size_t)cur.r * num_q_heads + cur.h * G) * kHeadDim,
+    const size_t out_row = ((size_t)cur.r * num_q_heads + cur.h * G) * kHeadDim;      // in elements
+    eng.finish(whole, PieceSink{static_cast<char*>(out) + out_row * (out_f32 ? 4 : 2), out_f32 != 0,
                                 part_acc + slot0 * kPartialFloats, part_ml + slot0});
     piece_lo = 0;                           // a new (r, h) starts with the next block
   };
@@ -693,7 +705,8 @@ __global__ __launch_bounds__(kWave * G) void decode_merge_kernel(const DecodeHea
                                                              const int4* __restrict__ wave_desc,
                                                              const float2* __restrict__ part_ml,
                                                              const float* __restrict__ part_acc,
-                                                             uint16_t* __restrict__ out, int32_t num_seqs,
+                                                             void* __restrict__ out, int32_t out_f32,
+                                                             int32_t num_seqs,
                                                              int32_t num_q_heads, int32_t num_kv_heads,
                                                              int32_t max_waves, int32_t max_tokens,
                                                              CounterJob job) {
@@ -712,8 +725,9 @@ __global__ __launch_bounds__(kWave * G) void decode_merge_kernel(const DecodeHea
   if ((int)blockIdx.x >= max_waves) {                    // empty sequences: all-zero rows
     const int r = blockIdx.x - max_waves;
     if (min(seq_lens[r], max_tokens) > 0) return;
-    uint32_t* dst = reinterpret_cast<uint32_t*>(out + (size_t)r * num_q_heads * kHeadDim);
-    for (int i = tid; i < num_q_heads * (kHeadDim / 2); i += kWave * G) dst[i] = 0u;
+    const int words = num_q_heads * (out_f32 ? kHeadDim : kHeadDim / 2);    // 4-byte words of one output row block
+    uint32_t* dst = static_cast<uint32_t*>(out) + (size_t)r * words;
+    for (int i = tid; i < words; i += kWave * G) dst[i] = 0u;
     return;
   }
   const int w = blockIdx.x;
@@ -744,8 +758,11 @@ __global__ __launch_bounds__(kWave * G) void decode_merge_kernel(const DecodeHea
       a1 = fmaf(a.y, wgt, a1);
     }
     const float inv = 1.f / l;
-    uint32_t* dst = reinterpret_cast<uint32_t*>(out + ((size_t)d.x * num_q_heads + d.y * group + g) * kHeadDim) + lane;
-    *dst = pack2<T>(a0 * inv, a1 * inv);
+    const size_t row = ((size_t)d.x * num_q_heads + d.y * group + g) * kHeadDim;       // in elements
+    if (out_f32)
+      reinterpret_cast<float2*>(static_cast<float*>(out) + row)[lane] = make_float2(a0 * inv, a1 * inv);
+    else
+      reinterpret_cast<uint32_t*>(static_cast<uint16_t*>(out) + row)[lane] = pack2<T>(a0 * inv, a1 * inv);
   }
 }
 
@@ -753,9 +770,17 @@ __global__ __launch_bounds__(kWave * G) void decode_merge_kernel(const DecodeHea
 template <typename T, int G, typename Engine>
 static int launch_typed(const vtc_attn_params& p, int32_t num_seqs, const void* q, const void* k_cache,
                         const void* v_cache, const int32_t* block_table, const int32_t* seq_lens, void* out,
-                        void* workspace, hipStream_t stream, hipEvent_t ev_begin, hipEvent_t ev_end,
-                        const CounterJob& job) {
-  const DecodeWorkspace ws = decode_workspace_layout(p, num_seqs, 0);
+                        void* workspace, int32_t max_waves, hipStream_t stream, hipEvent_t ev_begin,
+                        hipEvent_t ev_end, const CounterJob& job) {
+  // Grid = the waves the chip holds at once (never more, so no wave waits for a slot while the others are
+  // already half way through their share), or as many of them as the caller's workspace has room for.  The
+  // kernel's launch bounds guarantee kMinWavesPerSimd waves on each of a compute unit's four SIMDs.
+  constexpr int kWavesPerCu = 4 * Engine::kMinWavesPerSimd < kDecodeWavesPerCu ? 4 * Engine::kMinWavesPerSimd
+                                                                                : kDecodeWavesPerCu;
+  const long long resident = (long long)device_cu_count() * kWavesPerCu;
+  const int grid = (int)(resident < max_waves ? resident : max_waves);
+
+  const DecodeWorkspace ws = decode_workspace_layout(p, num_seqs, grid);
   char* base = static_cast<char*>(workspace);
   DecodeHeader* header = reinterpret_cast<DecodeHeader*>(base + ws.header_off);
   int32_t* seg_prefix = reinterpret_cast<int32_t*>(base + ws.seg_prefix_off);
@@ -763,67 +788,56 @@ static int launch_typed(const vtc_attn_params& p, int32_t num_seqs, const void* 
   float2* part_ml = reinterpret_cast<float2*>(base + ws.ml_off);
   float* part_acc = reinterpret_cast<float*>(base + ws.acc_off);
   const int32_t max_tokens = p.max_blocks_per_seq * kBlockSize;
-
-  // Grid = the waves the chip holds at once (never more, so no wave waits for a slot while
-  // the others are already half way through their share).
-  static const int waves_per_cu = [] {     // queried once per kernel instance (thread-safe static initialisation)
-    int occ = 0;
-    if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&occ, decode_attend_kernel<T, G, Engine>, kWave, 0) != hipSuccess || occ <= 0)
-      occ = 8;
-    return occ < VTC_DECODE_WAVES_PER_CU ? occ : VTC_DECODE_WAVES_PER_CU;
-  }();
-  long long resident = (long long)device_cu_count() * waves_per_cu;
-  const int grid = (int)(resident < kMaxDecodeWaves ? resident : kMaxDecodeWaves);
+  const int32_t out_f32 = p.out_dtype == VTC_F32 ? 1 : 0;
 
   const bool self_plan = num_seqs <= kSelfPlanMaxSeqs;
   if (!self_plan)
     hipLaunchKernelGGL(decode_plan_kernel, dim3(1), dim3(kPlanThreads), 0, stream, seq_lens, num_seqs,
                        p.num_kv_heads, max_tokens, grid, header, seg_prefix, wave_desc);
-  if (ev_begin && hipEventRecord(ev_begin, stream) != hipSuccess) return VTC_ERR_HIP;
+  if (ev_begin) (void)hipEventRecord(ev_begin, stream);      // a failure shows up in hipGetLastError() below
   hipLaunchKernelGGL((decode_attend_kernel<T, G, Engine>), dim3(grid), dim3(kWave), 0, stream,
                      static_cast<const uint16_t*>(q), static_cast<const uint16_t*>(k_cache),
-                     static_cast<const uint16_t*>(v_cache), block_table, seq_lens, static_cast<uint16_t*>(out),
+                     static_cast<const uint16_t*>(v_cache), block_table, seq_lens, out, out_f32,
                      wave_desc, part_ml, part_acc, p.num_kv_heads, p.max_blocks_per_seq, p.scale * kLog2e,
                      self_plan ? num_seqs : 0, header);
-  if (ev_end && hipEventRecord(ev_end, stream) != hipSuccess) return VTC_ERR_HIP;
+  if (ev_end) (void)hipEventRecord(ev_end, stream);
   const int counter_blocks = (job.n + kFusedCounterRequests - 1) / kFusedCounterRequests;
   hipLaunchKernelGGL((decode_merge_kernel<T, G>), dim3(grid + num_seqs + counter_blocks), dim3(kWave, G), 0, stream,
-                     header, seq_lens, wave_desc, part_ml, part_acc, static_cast<uint16_t*>(out), num_seqs,
+                     header, seq_lens, wave_desc, part_ml, part_acc, out, out_f32, num_seqs,
                      p.num_q_heads, p.num_kv_heads, grid, max_tokens, job);
   return hipGetLastError() == hipSuccess ? VTC_OK : VTC_ERR_HIP;
 }
 
-#if VTC_DECODE_GQA_MFMA
-template <typename T, int G>
-using GqaEngine = MfmaEngine<T, G>;
-#else
-template <typename T, int G>
-using GqaEngine = ValuEngine<T, G>;
-#endif
-
 template <typename T>
 static int launch_group(const vtc_attn_params& p, int32_t num_seqs, const void* q, const void* k_cache,
                         const void* v_cache, const int32_t* block_table, const int32_t* seq_lens, void* out,
-                        void* workspace, hipStream_t stream, hipEvent_t ev_begin, hipEvent_t ev_end,
-                        const CounterJob& job) {
+                        void* workspace, int32_t max_waves, hipStream_t stream, hipEvent_t ev_begin,
+                        hipEvent_t ev_end, const CounterJob& job) {
+#define VTC_DECODE_CASE(G, ENGINE)                                                                             \
+  case G:                                                                                                      \
+    return launch_typed<T, G, ENGINE<T, G>>(p, num_seqs, q, k_cache, v_cache, block_table, seq_lens, out,      \
+                                            workspace, max_waves, stream, ev_begin, ev_end, job)
   switch (p.num_q_heads / p.num_kv_heads) {
-    case 1: return launch_typed<T, 1, ValuEngine<T, 1>>(p, num_seqs, q, k_cache, v_cache, block_table, seq_lens, out, workspace, stream, ev_begin, ev_end, job);
-    case 2: return launch_typed<T, 2, GqaEngine<T, 2>>(p, num_seqs, q, k_cache, v_cache, block_table, seq_lens, out, workspace, stream, ev_begin, ev_end, job);
-    case 4: return launch_typed<T, 4, GqaEngine<T, 4>>(p, num_seqs, q, k_cache, v_cache, block_table, seq_lens, out, workspace, stream, ev_begin, ev_end, job);
-    case 8: return launch_typed<T, 8, GqaEngine<T, 8>>(p, num_seqs, q, k_cache, v_cache, block_table, seq_lens, out, workspace, stream, ev_begin, ev_end, job);
+    VTC_DECODE_CASE(1, ValuEngine);      // one query head per KV head: 1 flop per byte, vector ALUs
+    VTC_DECODE_CASE(2, MfmaEngine);      // grouped queries: the vector path becomes ALU-bound, matrix cores
+    VTC_DECODE_CASE(4, MfmaEngine);
+    VTC_DECODE_CASE(8, MfmaEngine);
     default: return VTC_ERR_UNSUPPORTED;
   }
+#undef VTC_DECODE_CASE
 }
 
 int launch_decode(const vtc_attn_params& p, int32_t num_seqs, const void* q, const void* k_cache,
                   const void* v_cache, const int32_t* block_table, const int32_t* seq_lens, void* out,
-                  void* workspace, hipStream_t stream, hipEvent_t ev_begin, hipEvent_t ev_end,
+                  void* workspace, int32_t max_waves, hipStream_t stream, hipEvent_t ev_begin, hipEvent_t ev_end,
                   const CounterJob& job) {
   // the flattened block index must fit the 64-bit products used above and the grid limits of the merge launch
   if ((long long)num_seqs * p.max_blocks_per_seq >= (1ll << 31)) return VTC_ERR_UNSUPPORTED;
   if (p.dtype == VTC_F16)
-    return launch_group<F16>(p, num_seqs, q, k_cache, v_cache, block_table, seq_lens, out, workspace, stream, ev_begin, ev_end, job);
-  return launch_group<BF16>(p, num_seqs, q, k_cache, v_cache, block_table, seq_lens, out, workspace, stream, ev_begin, ev_end, job);
+    return launch_group<F16>(p, num_seqs, q, k_cache, v_cache, block_table, seq_lens, out, workspace, max_waves, stream,
+                             ev_begin, ev_end, job);
+  return launch_group<BF16>(p, num_seqs, q, k_cache, v_cache, block_table, seq_lens, out, workspace, max_waves, stream,
+                            ev_begin, ev_end, job);
 }
 
 }  // namespace vtc

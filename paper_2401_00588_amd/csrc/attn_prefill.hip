@@ -33,22 +33,14 @@
 namespace vtc {
 
 using f32x16 = float __attribute__((ext_vector_type(16)));
+using f32x4 = float __attribute__((ext_vector_type(4)));
 using f16x8 = _Float16 __attribute__((ext_vector_type(8)));
 using bf16x8 = __bf16 __attribute__((ext_vector_type(8)));
 using s16x4 = short __attribute__((ext_vector_type(4)));
 using u32x2 = uint32_t __attribute__((ext_vector_type(2)));
 
-#ifndef VTC_PREFILL_SCHED_HINTS
-#define VTC_PREFILL_SCHED_HINTS 1
-#endif
-#ifndef VTC_PREFILL_QK_AHEAD
-#define VTC_PREFILL_QK_AHEAD 6
-#endif
-constexpr int kQkAhead = VTC_PREFILL_QK_AHEAD;   // K fragments in flight ahead of the product that uses them
-#ifndef VTC_PREFILL_PV_AHEAD
-#define VTC_PREFILL_PV_AHEAD 4
-#endif
-constexpr int kPvAhead = VTC_PREFILL_PV_AHEAD;   // V^T fragments in flight ahead of the product that uses them
+constexpr int kQkAhead = 6;              // K fragments in flight ahead of the product that uses them
+constexpr int kPvAhead = 4;              // V^T fragments in flight ahead of the product(s) that use them
 constexpr int kXcds = 8;                 // accelerator complex dies of an MI355X
 constexpr int kCusPerXcd = 32;           // compute units on each of them
 constexpr int kPfThreads = 256;
@@ -124,8 +116,8 @@ template <typename T, int HW, bool kPosScale>
 __global__ __launch_bounds__(kPfThreads, 2) void prefill_chunk_kernel(
     const uint16_t* __restrict__ q, const int32_t* __restrict__ cu_q_lens, const uint16_t* __restrict__ k_cache,
     const uint16_t* __restrict__ v_cache, const int32_t* __restrict__ block_table,
-    const int32_t* __restrict__ seq_lens, uint16_t* __restrict__ out, int32_t num_q_heads, int32_t num_kv_heads,
-    int32_t max_blocks_per_seq, float scale2) {
+    const int32_t* __restrict__ seq_lens, void* __restrict__ out, int32_t out_f32, int32_t num_q_heads,
+    int32_t num_kv_heads, int32_t max_blocks_per_seq, float scale2) {
   constexpr int TT = 4 / HW;                       // 32-token tiles per workgroup
   constexpr int kTokensPerWg = kPfRows * TT;
   __shared__ __attribute__((aligned(1024))) uint16_t lds[4 * kTileElems64];    // K buffers 0, 1, then V buffers 0, 1
@@ -176,6 +168,19 @@ __global__ __launch_bounds__(kPfThreads, 2) void prefill_chunk_kernel(
   asm volatile("" ::: "memory");                                   // keep the four loads together, ahead of their first use
   const int lq = q_end - q_begin;
   if (qt * kTokensPerWg >= lq) return;                             // uniform over the workgroup
+  if (min(max(s_raw, 0), max_blocks_per_seq * kBlockSize) < lq) {
+    // The context is shorter than the chunk that is said to end it: there is no position to give the chunk's
+    // tokens.  Their output rows are zeroed and nothing of the cache or the block table is touched.
+    const int words_per_row = out_f32 ? kHeadDim : kHeadDim / 2;   // 4-byte words of one (token, head) row
+    const int tok_lo = qt * kTokensPerWg, tok_hi = min(lq, tok_lo + kTokensPerWg);
+    const int group0 = num_q_heads / num_kv_heads;
+    const int head_lo = (slot / (group0 / HW)) * group0 + (slot % (group0 / HW)) * HW;
+    for (int i = tid; i < (tok_hi - tok_lo) * HW * words_per_row; i += kPfThreads) {
+      const int w = i % words_per_row, hh = (i / words_per_row) % HW, t = i / (words_per_row * HW);
+      static_cast<uint32_t*>(out)[((size_t)(q_begin + tok_lo + t) * num_q_heads + head_lo + hh) * words_per_row + w] = 0u;
+    }
+    return;
+  }
   const int group = num_q_heads / num_kv_heads;
   const int subs = group / HW;                                     // workgroups per kv head
   const int kvh = slot / subs;
@@ -282,7 +287,6 @@ __global__ __launch_bounds__(kPfThreads, 2) void prefill_chunk_kernel(
           sacc[sb] = mfma32<T>(kf, qf[ks], sacc[sb]);
         }
       }
-#if VTC_PREFILL_SCHED_HINTS
       // order of the 16 fragment reads and 16 products above: reads run kQkAhead fragments ahead of their use
       __builtin_amdgcn_sched_group_barrier(0x100, kQkAhead, 0);
 #pragma unroll
@@ -291,7 +295,6 @@ __global__ __launch_bounds__(kPfThreads, 2) void prefill_chunk_kernel(
         __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
       }
       __builtin_amdgcn_sched_group_barrier(0x008, kQkAhead, 0);
-#endif
       // ---- causal mask (only tiles that reach past the wave's first query position), row maximum
       const float masked = kPosScale ? -INFINITY : INFINITY;
       if (k0 + kPfKTile - 1 > p0 + tok0) {
@@ -315,8 +318,12 @@ __global__ __launch_bounds__(kPfThreads, 2) void prefill_chunk_kernel(
       const float alpha = fast_exp2(m_run - m_sub);
       m_run = m_new;
       // ---- P^T = exp2(scaled logit - m), packed to the storage type as the B operands
+      // bf16 keeps 8 bits of a weight.  What the rounding drops enters the second product as an operand of its
+      // own (pr), so the weights act with 16 bits; fp16's 11 bits are left as they are.
+      constexpr bool kSplitP = __is_same(T, BF16);
       float psum = 0.f;
       u32x4 pb[2][2];
+      u32x4 pr[kSplitP ? 2 : 1][2];
       constexpr uint32_t kOnes = __is_same(T, F16) ? 0x3c003c00u : 0x3f803f80u;   // (1, 1) in the storage type
 #pragma unroll
       for (int sb = 0; sb < 2; ++sb)
@@ -326,10 +333,17 @@ __global__ __launch_bounds__(kPfThreads, 2) void prefill_chunk_kernel(
           for (int w = 0; w < 4; ++w) {
             const float pa = fast_exp2(fmaf(sacc[sb][8 * t + 2 * w], scale2, -m_sub));
             const float pc = fast_exp2(fmaf(sacc[sb][8 * t + 2 * w + 1], scale2, -m_sub));
-            pb[sb][t][w] = pack2<T>(pa, pc);
+            const uint32_t hi = pack2<T>(pa, pc);
+            pb[sb][t][w] = hi;
             // the row sum adds up the weights as the second product will see them (after rounding to the
             // storage type), so the output stays an exact convex combination of the V rows
-            psum = dot2<T>(pb[sb][t][w], kOnes, psum);
+            psum = dot2<T>(hi, kOnes, psum);
+            if constexpr (kSplitP) {
+              const uint32_t lo = pack2<T>(pa - __builtin_bit_cast(float, hi << 16),
+                                           pc - __builtin_bit_cast(float, hi & 0xffff0000u));
+              pr[sb][t][w] = lo;
+              psum = dot2<T>(lo, kOnes, psum);
+            }
           }
       l_run = l_run * alpha + psum;
       if (__builtin_amdgcn_ballot_w64(alpha != 1.f) != 0ull) {      // skip the rescale when no row's maximum moved
@@ -353,20 +367,21 @@ __global__ __launch_bounds__(kPfThreads, 2) void prefill_chunk_kernel(
             const int dofs = 32 * (db ^ tr_row);
             const u32x2 lo = lds_read_tr16(vrow + dofs);                       // keys 16t+4hg+0..3
             const u32x2 hi = lds_read_tr16(vrow + 8 * kHeadDim + dofs);        // keys 16t+8+4hg+0..3
-            oacc[db] = mfma32<T>(u32x4{lo[0], lo[1], hi[0], hi[1]}, pb[sb][t], oacc[db]);
+            const u32x4 vt = u32x4{lo[0], lo[1], hi[0], hi[1]};
+            oacc[db] = mfma32<T>(vt, pb[sb][t], oacc[db]);
+            if constexpr (kSplitP) oacc[db] = mfma32<T>(vt, pr[sb][t], oacc[db]);
           }
         }
-#if VTC_PREFILL_SCHED_HINTS
-      // order of the 32 transposing reads and 16 products above: kPvAhead fragments (2 reads each) ahead of use;
-      // the first reads may start while the weights are still being exponentiated
+      // order of the 32 transposing reads and the 16 (bf16: 32) products above: kPvAhead fragments (2 reads each)
+      // ahead of use; the first reads may start while the weights are still being exponentiated
+      constexpr int kPerFrag = kSplitP ? 2 : 1;                     // products that consume one V^T fragment
       __builtin_amdgcn_sched_group_barrier(0x100, 2 * kPvAhead, 0);
 #pragma unroll
       for (int i = 0; i < 16 - kPvAhead; ++i) {
-        __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+        __builtin_amdgcn_sched_group_barrier(0x008, kPerFrag, 0);
         __builtin_amdgcn_sched_group_barrier(0x100, 2, 0);
       }
-      __builtin_amdgcn_sched_group_barrier(0x008, kPvAhead, 0);
-#endif
+      __builtin_amdgcn_sched_group_barrier(0x008, kPerFrag * kPvAhead, 0);
     }
 
   };
@@ -401,6 +416,21 @@ __global__ __launch_bounds__(kPfThreads, 2) void prefill_chunk_kernel(
   if (wave_has_rows) {
     uint16_t* patch = lds + wave * (kPfRows * kPitchO);
     const float inv = l_run > 0.f ? 1.f / l_run : 0.f;
+    if (out_f32) {
+      // fp32 rows, no rounding: the lane's 4 consecutive dims go out as one 16-byte store (the two lane halves
+      // of a row fill 32 contiguous bytes per instruction)
+      if (i_row < lq) {
+        float* dst = static_cast<float*>(out) + ((size_t)(q_begin + i_row) * num_q_heads + h) * kHeadDim + 4 * hg;
+#pragma unroll
+        for (int db = 0; db < 4; ++db)
+#pragma unroll
+          for (int j = 0; j < 4; ++j)
+            __builtin_nontemporal_store(
+                f32x4{oacc[db][4 * j] * inv, oacc[db][4 * j + 1] * inv, oacc[db][4 * j + 2] * inv, oacc[db][4 * j + 3] * inv},
+                reinterpret_cast<f32x4*>(dst + db * 32 + 8 * j));
+      }
+      return;
+    }
 #pragma unroll
     for (int db = 0; db < 4; ++db)
 #pragma unroll
@@ -417,7 +447,7 @@ __global__ __launch_bounds__(kPfThreads, 2) void prefill_chunk_kernel(
       const u32x4 v = *reinterpret_cast<const u32x4*>(&patch[row * kPitchO + (lane & 15) * 8]);
       if (tok0 + row < lq)
         // (written once and not read again here: non-temporal, so that it does not displace K/V tiles from the L2)
-        __builtin_nontemporal_store(v, reinterpret_cast<u32x4*>(out + ((size_t)(q_begin + tok0 + row) * num_q_heads + h) * kHeadDim + (lane & 15) * 8));
+        __builtin_nontemporal_store(v, reinterpret_cast<u32x4*>(static_cast<uint16_t*>(out) + ((size_t)(q_begin + tok0 + row) * num_q_heads + h) * kHeadDim + (lane & 15) * 8));
     }
   }
 }
@@ -436,8 +466,8 @@ static int launch_hw(const vtc_attn_params& p, int32_t num_seqs, const void* q, 
   auto go = [&](auto kernel) {
     hipLaunchKernelGGL(kernel, grid, dim3(kPfThreads), 0, stream, static_cast<const uint16_t*>(q), cu_q_lens,
                        static_cast<const uint16_t*>(k_cache), static_cast<const uint16_t*>(v_cache), block_table,
-                       seq_lens, static_cast<uint16_t*>(out), p.num_q_heads, p.num_kv_heads, p.max_blocks_per_seq,
-                       scale2);
+                       seq_lens, out, p.out_dtype == VTC_F32 ? 1 : 0, p.num_q_heads, p.num_kv_heads,
+                       p.max_blocks_per_seq, scale2);
   };
   if (scale2 >= 0.f)
     go(prefill_chunk_kernel<T, HW, true>);

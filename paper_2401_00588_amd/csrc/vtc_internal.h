@@ -15,32 +15,10 @@ constexpr int kWave = 64;           // CDNA wavefront
 constexpr int kTileElems = kBlockSize * kHeadDim;   // elements of one (block, kv head) K or V tile
 constexpr float kLog2e = 1.4426950408889634f;
 
-// Build-time tunables of the decode kernel (override with -D for experiments).
-#ifndef VTC_DECODE_WAVES_PER_CU
-#define VTC_DECODE_WAVES_PER_CU 16       // waves launched per compute unit (capped by occupancy)
-#endif
-#ifndef VTC_DECODE_NT_LOADS
-#define VTC_DECODE_NT_LOADS 1            // 1: stream K/V with non-temporal loads
-#endif
-#ifndef VTC_DECODE_GQA_MFMA
-#define VTC_DECODE_GQA_MFMA 1            // 1: grouped-query decode runs its two small products on the matrix cores
-#endif
-#ifndef VTC_DECODE_MFMA_WAVES_PER_SIMD
-#define VTC_DECODE_MFMA_WAVES_PER_SIMD 2 // occupancy target of the matrix-core decode engine
-#endif
-#ifndef VTC_DECODE_MIN_BLOCKS_PER_WAVE
-#define VTC_DECODE_MIN_BLOCKS_PER_WAVE 2 // small batches use fewer waves rather than shorter ranges
-#endif
-#ifndef VTC_DECODE_BF16_SPLIT_P
-#define VTC_DECODE_BF16_SPLIT_P 1        // 1: the matrix-core engine feeds bf16 weights as two operands (16 bits)
-#endif
-#ifndef VTC_DECODE_SELF_PLAN
-#define VTC_DECODE_SELF_PLAN 1           // 1: batches of <= 1024 sequences skip the planning launch
-#endif
-
-// Decode attention cuts the batch's stream of KV blocks into one range per wave.
-constexpr int kMaxDecodeWaves = 8192;                          // upper bound on the launch, sizes the workspace
-constexpr int kMinBlocksPerWave = VTC_DECODE_MIN_BLOCKS_PER_WAVE;
+// Decode attention cuts the batch's stream of KV blocks into one range per resident wave.
+constexpr int kDecodeWavesPerCu = 16;        // waves launched per compute unit, at most (fewer where registers limit it)
+constexpr int kMaxDecodeWaves = 8192;        // upper bound on the launch on any device
+constexpr int kMinBlocksPerWave = 2;         // small batches use fewer waves rather than shorter ranges
 
 // One fp32 partial result of a piece: running max m (log2 domain), sum l, acc[128].
 constexpr int kPartialFloats = kHeadDim;
@@ -129,33 +107,64 @@ __device__ __forceinline__ float fast_exp2(float x) { return __builtin_amdgcn_ex
 // ---- host side --------------------------------------------------------------
 struct DecodeWorkspace {
   size_t header_off;        // DecodeHeader
-  size_t seg_prefix_off;    // int32 [num_seqs + 1]          exclusive prefix of KV blocks per sequence
-  size_t wave_desc_off;     // int4  [kMaxDecodeWaves]       (r, h, b, n_blocks): start and length of a wave's range
-  size_t ml_off;            // float2[2 * kMaxDecodeWaves * G] (m, l) of each partial piece
-  size_t acc_off;           // float [2 * kMaxDecodeWaves * G * 128]
+  size_t seg_prefix_off;    // int32 [num_seqs + 1]      exclusive prefix of KV blocks per sequence
+  size_t wave_desc_off;     // int4  [max(waves, 64)]    (r, h, b, n_blocks): start and length of a wave's range
+  size_t ml_off;            // float2[2 * waves * G]     (m, l) of each partial piece
+  size_t acc_off;           // float [2 * waves * G * 128]
   size_t total_bytes;
 };
 
 inline size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
 
-// The footprint depends on the number of sequences and on Hq/Hkv only: a wave owns at most
-// two partial pieces however long the contexts are.
-inline DecodeWorkspace decode_workspace_layout(const vtc_attn_params& p, int32_t num_seqs, int32_t /*max_seq_len*/) {
+int device_cu_count();   // compute units of the current device (cached per device; 256 when there is no device)
+
+// The most waves a decode launch uses on the current device.
+inline int decode_wave_bound() {
+  const long long w = (long long)device_cu_count() * kDecodeWavesPerCu;
+  return (int)(w < kMaxDecodeWaves ? w : kMaxDecodeWaves);
+}
+
+// Layout for a launch of `waves` waves over num_seqs sequences.  A wave owns at most two partial pieces
+// however long the contexts are, so the footprint is linear in the number of waves.
+inline DecodeWorkspace decode_workspace_layout(const vtc_attn_params& p, int32_t num_seqs, int32_t waves) {
   const size_t group = (size_t)(p.num_q_heads / p.num_kv_heads);
-  DecodeWorkspace w{};
+  const size_t w = (size_t)(waves > 0 ? waves : 0);
+  DecodeWorkspace ws{};
   size_t at = 0;
-  w.header_off = at;
+  ws.header_off = at;
   at = 256;
-  w.seg_prefix_off = at;
+  ws.seg_prefix_off = at;
   at = align_up(at + sizeof(int32_t) * ((size_t)num_seqs + 1), 256);
-  w.wave_desc_off = at;
-  at = align_up(at + sizeof(int32_t) * 4 * (size_t)kMaxDecodeWaves, 256);
-  w.ml_off = at;
-  at = align_up(at + sizeof(float) * 2 * 2 * (size_t)kMaxDecodeWaves * group, 256);
-  w.acc_off = at;
-  at = align_up(at + sizeof(float) * kPartialFloats * 2 * (size_t)kMaxDecodeWaves * group, 256);
-  w.total_bytes = at;
-  return w;
+  ws.wave_desc_off = at;
+  at = align_up(at + sizeof(int32_t) * 4 * (w > 64 ? w : 64), 256);    // at least 1 KiB: also the target of dummy prefetches
+  ws.ml_off = at;
+  at = align_up(at + sizeof(float) * 2 * 2 * w * group, 256);
+  ws.acc_off = at;
+  at = align_up(at + sizeof(float) * kPartialFloats * 2 * w * group, 256);
+  ws.total_bytes = at;
+  return ws;
+}
+
+// Waves that a launch over sequences of at most max_seq_len tokens can put to use (0 or less: the block
+// table's capacity): every wave gets at least kMinBlocksPerWave KV blocks.
+inline int decode_waves_for(const vtc_attn_params& p, int32_t num_seqs, int32_t max_seq_len) {
+  const long long cap = (long long)p.max_blocks_per_seq;
+  long long nb = max_seq_len > 0 ? ((long long)max_seq_len + kBlockSize - 1) / kBlockSize : cap;
+  if (nb > cap) nb = cap;
+  const long long want = (nb * num_seqs * p.num_kv_heads + kMinBlocksPerWave - 1) / kMinBlocksPerWave;
+  const long long bound = decode_wave_bound();
+  const long long w = want < bound ? want : bound;
+  return (int)(w > 1 ? w : 1);
+}
+
+// The most waves (<= limit) whose layout fits into `bytes`; 0 if not even one does.
+inline int decode_wave_capacity(const vtc_attn_params& p, int32_t num_seqs, size_t bytes, int limit) {
+  int lo = 0, hi = limit;                      // the footprint is monotone in the number of waves
+  while (lo < hi) {
+    const int mid = lo + (hi - lo + 1) / 2;
+    if (decode_workspace_layout(p, num_seqs, mid).total_bytes <= bytes) lo = mid; else hi = mid - 1;
+  }
+  return lo;
 }
 
 // Host-side validation of the parameter struct; no HIP calls.
@@ -168,10 +177,9 @@ inline int check_params(const vtc_attn_params* p) {
   if (g != 1 && g != 2 && g != 4 && g != 8) return VTC_ERR_UNSUPPORTED;
   if (p->head_dim != kHeadDim || p->block_size != kBlockSize) return VTC_ERR_UNSUPPORTED;
   if (p->dtype != VTC_F16 && p->dtype != VTC_BF16) return VTC_ERR_UNSUPPORTED;
+  if (p->out_dtype != p->dtype && p->out_dtype != VTC_F32) return VTC_ERR_UNSUPPORTED;
   return VTC_OK;
 }
-
-int device_cu_count();   // compute units of the current device (cached per device)
 
 // A counter update that rides in the last launch of a decode step (Algorithm 2 charges the
 // counters right after forward_decode).  n == 0: none.
@@ -188,7 +196,7 @@ struct CounterJob {
 // Kernel launchers (one translation unit each).
 int launch_decode(const vtc_attn_params& p, int32_t num_seqs, const void* q, const void* k_cache,
                   const void* v_cache, const int32_t* block_table, const int32_t* seq_lens, void* out,
-                  void* workspace, hipStream_t stream, hipEvent_t ev_begin, hipEvent_t ev_end,
+                  void* workspace, int32_t max_waves, hipStream_t stream, hipEvent_t ev_begin, hipEvent_t ev_end,
                   const CounterJob& counter_job);
 int launch_prefill(const vtc_attn_params& p, int32_t num_seqs, const void* q, const int32_t* cu_q_lens,
                    int32_t max_q_len, const void* k_cache, const void* v_cache, const int32_t* block_table,

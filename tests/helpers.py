@@ -50,23 +50,155 @@ def bits_to_f64_via_torch(bits: np.ndarray, dtype: str) -> np.ndarray:
 
 # ---- the floating-point bar of the GPU parity tests ---------------------------------------------------
 TOL = {"f16": 2e-3, "bf16": 1e-2}          # max-abs against the unrounded fp64 oracle
+FORMAT_LIMIT = 4.0                         # |o| from which a 16-bit output format cannot meet TOL by rounding alone
 _MANTISSA_BITS = {"f16": 10, "bf16": 7}
 
 
 def elementwise_tolerance(want: np.ndarray, dtype: str) -> np.ndarray:
-    """The bound every output element is held to.
+    """The bound an output element *stored in the 16-bit format* is held to.
 
-    It is the flat max-abs tolerance wherever the output format can express a result that close.  From
-    |o| >= 4 on it cannot: there the spacing of bf16 is 2^-5 (of fp16 2^-8), so even the correctly
-    rounded exact result may be off by half of that, 1.56e-2 (1.95e-3).  Such elements -- a handful per
-    million with N(0,1) values and very few keys -- are held to half a unit in the last place of the
-    output format plus a fifth of the flat tolerance for the arithmetic before the final rounding.
+    It is the flat max-abs tolerance for every |o| < 4.  From |o| >= 4 on the format cannot express a
+    result that close: there the spacing of bf16 is 2^-5 (of fp16 2^-8), so even the correctly rounded
+    exact result may be off by half of that, 1.56e-2 (1.95e-3).  Such elements -- a handful per million
+    with N(0,1) values and very few keys -- are held to half a unit in the last place of the output
+    format plus a fifth of the flat tolerance for the arithmetic before the final rounding.  Results
+    returned as fp32 (``out_dtype = VTC_F32``) are held to the flat tolerance everywhere instead.
     """
     a = np.maximum(np.abs(np.asarray(want, dtype=np.float64)), 2.0 ** -24)
     half_ulp = 0.5 * np.exp2(np.floor(np.log2(a)) - _MANTISSA_BITS[dtype])
-    return np.maximum(TOL[dtype], half_ulp + 0.2 * TOL[dtype])
+    return np.where(a < FORMAT_LIMIT, TOL[dtype], half_ulp + 0.2 * TOL[dtype])
+
+
+def parity_stats(got: np.ndarray, want: np.ndarray, dtype: str) -> dict:
+    """Error figures of a 16-bit-format result against the oracle (see ``elementwise_tolerance``)."""
+    got = np.asarray(got, dtype=np.float64)
+    want = np.asarray(want, dtype=np.float64)
+    err = np.abs(got - want)
+    finite = bool(np.isfinite(got).all())
+    return {
+        "max_abs": float(err.max()) if err.size and finite else (0.0 if finite else float("inf")),
+        "elements": int(err.size),
+        "format_limited": int((np.abs(want) >= FORMAT_LIMIT).sum()),     # elements allowed the format's own bound
+        "over_flat": int((err > TOL[dtype]).sum()) if finite else int(err.size),   # elements that needed it
+        "ok": bool(finite and (err <= elementwise_tolerance(want, dtype)).all()),
+    }
 
 
 def within_tolerance(got: np.ndarray, want: np.ndarray, dtype: str) -> bool:
+    return parity_stats(got, want, dtype)["ok"]
+
+
+def check_storage_output(got: np.ndarray, want: np.ndarray, dtype: str, label: str, flat_only: bool = False) -> dict:
+    """Assert a result stored as fp16 / bf16 against the oracle and print how the bound was used.
+
+    Every element with |o| < 4 meets the flat tolerance; ``flat_only`` asserts that there is no other
+    element (true of every benchmark configuration, whose contexts keep |o| small).
+    """
+    st = parity_stats(got, want, dtype)
+    print(f"  {label}: {dtype} output, max abs err {st['max_abs']:.3e} (flat bar {TOL[dtype]:.0e}); "
+          f"{st['format_limited']} of {st['elements']} elements have |o| >= {FORMAT_LIMIT:g}, "
+          f"{st['over_flat']} exceed the flat bar", flush=True)
+    assert st["ok"], f"{label}: outside the tolerance ({st})"
+    assert st["over_flat"] <= st["format_limited"]
+    if flat_only:
+        assert st["format_limited"] == 0 and st["over_flat"] == 0 and st["max_abs"] <= TOL[dtype], f"{label}: {st}"
+    return st
+
+
+def check_f32_output(got: np.ndarray, want: np.ndarray, dtype: str, label: str) -> float:
+    """Assert a result returned as fp32 against the oracle: the flat tolerance on every element."""
     got = np.asarray(got, dtype=np.float64)
-    return bool(np.isfinite(got).all() and (np.abs(got - want) <= elementwise_tolerance(want, dtype)).all())
+    assert np.isfinite(got).all(), f"{label}: non-finite fp32 output"
+    err = float(np.abs(got - np.asarray(want, dtype=np.float64)).max()) if got.size else 0.0
+    print(f"  {label}: fp32 output, max abs err {err:.3e} (flat bar {TOL[dtype]:.0e})", flush=True)
+    assert err <= TOL[dtype], f"{label}: fp32 output off by {err:.3e} > {TOL[dtype]:.0e}"
+    return err
+
+
+def check_both_outputs(out16, out32, want: np.ndarray, dtype: str, label: str, flat_only: bool = False) -> np.ndarray:
+    """The same call made with 16-bit and with fp32 output rows (torch tensors) against the oracle.
+
+    fp32 rows: flat tolerance everywhere.  16-bit rows: ``check_storage_output``; and they are the
+    fp32 rows rounded once to nearest even, bit for bit.  Returns the 16-bit result widened to float64.
+    """
+    import torch
+
+    from workloads import tensor_to_bits
+
+    assert out32.dtype == torch.float32 and out16.shape == out32.shape
+    check_f32_output(out32.detach().cpu().double().numpy(), want, dtype, label)
+    bits16 = tensor_to_bits(out16)
+    t = out16.dtype
+    got16 = out16.detach().cpu().double().numpy()
+    check_storage_output(got16, want, dtype, label, flat_only=flat_only)
+    assert np.array_equal(bits16, tensor_to_bits(out32.to(t))), f"{label}: 16-bit rows are not the rounded fp32 rows"
+    return got16
+
+
+# ---- the oracle over a whole configuration, threaded over requests ------------------------------------
+def _compact_blocks(cache, table_rows, seq_lens, block_size):
+    """Host copy (uint16 bits) of only the blocks the given sequences use, with a block table renumbered to match."""
+    import torch
+
+    from workloads import tensor_to_bits
+
+    need = [(int(s) + block_size - 1) // block_size for s in seq_lens]
+    width = max(need + [1])
+    table = np.zeros((len(need), width), dtype=np.int32)
+    picks, at = [], 0
+    for i, n in enumerate(need):
+        picks.append(table_rows[i, :n].long())
+        table[i, :n] = np.arange(at, at + n)
+        at += n
+    idx = torch.cat(picks) if picks else torch.zeros(0, dtype=torch.long, device=cache.device)
+    return tensor_to_bits(cache[idx]), table
+
+
+def _threads() -> int:
+    import os
+
+    return max(1, min(16, os.cpu_count() or 1))
+
+
+def full_decode_oracle(st, scale: float) -> np.ndarray:
+    """fp64 oracle output [Nd, Hq, D] of the decode half of a device step, every request and head."""
+    from concurrent.futures import ThreadPoolExecutor
+
+    from oracle import attention as OA
+    from workloads import tensor_to_bits
+
+    b = st.batch
+    sh = b.shape
+    k_bits, table = _compact_blocks(st.k_cache, st.block_table, b.seq_lens, sh.block_size)
+    v_bits, _ = _compact_blocks(st.v_cache, st.block_table, b.seq_lens, sh.block_size)
+    q_bits = tensor_to_bits(st.q)
+    seq = [int(x) for x in b.seq_lens]
+
+    def one(i):
+        return OA.paged_decode(q_bits[i:i + 1], k_bits, v_bits, table[i:i + 1], seq[i:i + 1], scale, sh.dtype)[0]
+
+    with ThreadPoolExecutor(max_workers=_threads()) as pool:
+        return np.stack(list(pool.map(one, range(len(seq)))))
+
+
+def full_prefill_oracle(st, scale: float) -> np.ndarray:
+    """fp64 oracle output [T, Hq, D] of the prefill half of a device step, every chunk token and head."""
+    from concurrent.futures import ThreadPoolExecutor
+
+    from oracle import attention as OA
+    from workloads import tensor_to_bits
+
+    b = st.batch
+    sh = b.shape
+    k_bits, table = _compact_blocks(st.k_cache, st.pf_block_table, b.pf_seq_lens, sh.block_size)
+    v_bits, _ = _compact_blocks(st.v_cache, st.pf_block_table, b.pf_seq_lens, sh.block_size)
+    q_bits = tensor_to_bits(st.pf_q)
+    cu = st.pf_cu_q_lens.cpu().numpy()
+
+    def one(r):
+        lo, hi = int(cu[r]), int(cu[r + 1])
+        return OA.paged_prefill_chunk(q_bits[lo:hi], [0, hi - lo], k_bits, v_bits, table[r:r + 1],
+                                      [int(b.pf_seq_lens[r])], scale, sh.dtype)
+
+    with ThreadPoolExecutor(max_workers=_threads()) as pool:
+        return np.concatenate(list(pool.map(one, range(b.num_prefill))), axis=0)

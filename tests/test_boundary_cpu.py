@@ -45,8 +45,10 @@ def test_version_and_strerror(lib):
 
 def good_params(**kw):
     base = dict(num_q_heads=32, num_kv_heads=8, head_dim=128, block_size=16, max_blocks_per_seq=256,
-                dtype=vtc.VTC_BF16, scale=0.0883883461356163)
+                dtype=vtc.VTC_BF16, scale=0.0883883461356163, out_dtype=vtc.VTC_BF16)
     base.update(kw)
+    if "dtype" in kw and "out_dtype" not in kw:
+        base["out_dtype"] = kw["dtype"]
     return AttnParams(**base)
 
 
@@ -55,16 +57,21 @@ def test_workspace_bytes_is_host_arithmetic(lib):
     small = vtc.vtc_attn_workspace_bytes(p, 8, 256)
     big = vtc.vtc_attn_workspace_bytes(p, 512, 4096)
     assert 0 < small < big
-    # the footprint does not grow with the context length: a wave owns at most two partial results
+    # short batches cannot use many waves; from some size on the device's wave count caps the footprint
     assert vtc.vtc_attn_workspace_bytes(p, 512, 0) == big == vtc.vtc_attn_workspace_bytes(p, 512, 10 ** 9)
-    assert big % 256 == 0
+    assert vtc.vtc_attn_workspace_bytes(p, 4096, 0) - big <= 4 * 4096 + 256          # only the per-sequence prefix grows
+    assert big % 256 == 0 and small % 256 == 0
     # room for two fp32 partials (128 floats + m, l) per q head of the group for every wave of the largest launch
-    assert big >= 2 * 8192 * 4 * (128 + 2) * 4
-    assert big < 64 << 20
+    # (no device here: 256 compute units x 16 waves are assumed)
+    assert big >= 2 * 4096 * 4 * (128 + 2) * 4
+    assert big < 32 << 20
+    # 8 sequences x 16 blocks x 8 kv heads = 1024 blocks: 512 waves of two blocks each
+    assert 2 * 512 * 4 * (128 + 2) * 4 <= small < 2 * 512 * 4 * (128 + 2) * 4 + 16 * 512 + 4096
     mha = vtc.vtc_attn_workspace_bytes(good_params(num_q_heads=32, num_kv_heads=32), 512, 4096)
     assert mha < big                                   # fewer q heads share a KV head
     assert vtc.vtc_attn_workspace_bytes(good_params(head_dim=64), 8, 256) == 0
     assert lib.vtc_attn_workspace_bytes(None, 8, 256) == 0
+    assert vtc.vtc_attn_workspace_bytes(good_params(out_dtype=vtc.VTC_F32), 512, 4096) == big
 
 
 @pytest.mark.parametrize("kw,code", [
@@ -72,6 +79,7 @@ def test_workspace_bytes_is_host_arithmetic(lib):
     (dict(num_q_heads=32, num_kv_heads=5), -2), (dict(num_q_heads=48, num_kv_heads=16), -2),
     (dict(num_q_heads=0), -1), (dict(num_kv_heads=-1), -1), (dict(max_blocks_per_seq=0), -1),
     (dict(scale=float("nan")), -1),
+    (dict(out_dtype=vtc.VTC_F16), -2), (dict(out_dtype=5), -2), (dict(dtype=vtc.VTC_F32, out_dtype=vtc.VTC_F32), -2),
 ])
 def test_bad_params_are_rejected_by_every_attention_entry_point(lib, kw, code):
     p = good_params(**kw)
@@ -94,7 +102,10 @@ def test_null_pointers_sizes_alignment_and_workspace(lib):
         args = [a] * 7
         args[hole] = None
         assert lib.vtc_attn_decode(ctypes.byref(p), 4, *args, need, None) == -1
-    assert lib.vtc_attn_decode(ctypes.byref(p), 4, a, a, a, a, a, a, a, need - 1, None) == -3
+    one_wave = vtc.vtc_attn_workspace_bytes(p, 4, 1)
+    assert 0 < one_wave <= need
+    assert lib.vtc_attn_decode(ctypes.byref(p), 4, a, a, a, a, a, a, a, 1024, None) == -3      # not even one wave's share
+    assert lib.vtc_attn_decode(ctypes.byref(p), 4, a, a, a, a, a, a, a, 0, None) == -3
     assert lib.vtc_attn_decode(ctypes.byref(p), 4, a, a, a, a, a, a, ctypes.c_void_p(4096 + 64), need, None) == -1
     assert lib.vtc_attn_decode(ctypes.byref(p), 4, ctypes.c_void_p(4098), a, a, a, a, a, a, need, None) == -1
 
@@ -173,7 +184,7 @@ def test_fused_step_validates_both_halves_before_enqueueing(lib):
         attn[hole] = None
         assert call(attn=attn) == -1
     assert call(ws=None) == -1
-    assert call(ws_bytes=need - 1) == -3
+    assert call(ws_bytes=512) == -3
     assert call(ws=ctypes.c_void_p(4096 + 64)) == -1
     # nothing to do at all is a successful no-op, whatever the pointers are
     assert lib.vtc_step_decode(ctypes.byref(p), 0, None, None, None, None, None, None, None, 3, None, None, None, 0,

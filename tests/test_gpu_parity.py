@@ -1,9 +1,13 @@
 """Parity of the HIP path with the CPU oracle, through the C ABI (needs an MI355X).
 
-Tolerances (max-abs against the *unrounded* fp64 oracle): 2e-3 for fp16, 1e-2 for
-bf16, held elementwise (tests/helpers.py: from |o| >= 4 on the output format itself
-cannot meet them and the bound follows its spacing).  Counters and slot indices
-are compared bit for bit.
+Tolerances (max-abs against the *unrounded* fp64 oracle): 2e-3 for fp16 inputs, 1e-2
+for bf16 inputs.  Every attention case runs twice on the same inputs: with fp32 output
+rows, held to that flat bar on every element, and with output rows in the 16-bit
+storage format, held to the flat bar for every |o| < 4 (beyond that the format's own
+spacing exceeds it; tests/helpers.py prints how many elements that concerns) and
+required to be the fp32 rows rounded once.  The benchmark configurations are compared
+on every output element and must meet the flat bar throughout.  Counters and slot
+indices are compared bit for bit.
 """
 import math
 import sys
@@ -15,7 +19,7 @@ import paper_2401_00588_amd as vtc
 from oracle import attention as OA
 from oracle.counters import counter_update as oracle_counter_update
 from oracle.counters import gather_slots as oracle_gather_slots
-from tests.helpers import TOL, within_tolerance
+from tests.helpers import (TOL, check_both_outputs, full_decode_oracle, full_prefill_oracle)
 from workloads import (NAN_BITS, bits_to_tensor, make_block_table, make_device_step, make_qkv_numpy,
                        make_step_batch, poison_unused_rows, sequence_rows_to_host, tensor_to_bits)
 
@@ -100,19 +104,21 @@ def test_gathered_slots_are_bit_exact(torch):
 
 
 # -------------------------------------------------------------------- decode
-def _decode_case(torch, seq_lens, hq, hkv, dtype, seed, poison=False, min_row_len=0, scale=SCALE):
+def _decode_case(torch, seq_lens, hq, hkv, dtype, seed, poison=False, min_row_len=0, scale=SCALE, label="decode"):
+    """One decode call with 16-bit and one with fp32 output rows, both checked against the oracle."""
     rng = np.random.default_rng(seed)
     table, nb = make_block_table(rng, seq_lens, 16, min_row_len=min_row_len)
     q, k, v = make_qkv_numpy(rng, len(seq_lens), hq, hkv, 128, nb, 16, dtype)
     if poison:
         poison_unused_rows(k, table, seq_lens, NAN_BITS[dtype])
         poison_unused_rows(v, table, seq_lens, NAN_BITS[dtype])
-    p = vtc.make_params(hq, hkv, 128, 16, table.shape[1], dtype, scale)
-    out = vtc.vtc_attn_decode(p, bits_to_tensor(q, dtype), bits_to_tensor(k, dtype), bits_to_tensor(v, dtype),
-                              _i32(torch, table), _i32(torch, seq_lens))
+    args = (bits_to_tensor(q, dtype), bits_to_tensor(k, dtype), bits_to_tensor(v, dtype), _i32(torch, table),
+            _i32(torch, seq_lens))
+    out16 = vtc.vtc_attn_decode(vtc.make_params(hq, hkv, 128, 16, table.shape[1], dtype, scale), *args)
+    out32 = vtc.vtc_attn_decode(vtc.make_params(hq, hkv, 128, 16, table.shape[1], dtype, scale, "f32"), *args)
     torch.cuda.synchronize()
-    got = OA.widen(tensor_to_bits(out), dtype)
     want = OA.paged_decode(q, k, v, table, seq_lens, scale, dtype)
+    got = check_both_outputs(out16, out32, want, dtype, label)
     return got, want
 
 
@@ -126,7 +132,6 @@ def test_decode_ragged_lengths_match_the_oracle(torch, dtype, hq, hkv):
     got, want = _decode_case(torch, RAGGED, hq, hkv, dtype, seed=31)
     err = np.abs(got - want).max()
     say(f"  max abs err {err:.3e}  max |o| {np.abs(want).max():.3f}")
-    assert within_tolerance(got, want, dtype)
 
 
 @pytest.mark.parametrize("dtype,hq,hkv", [("f16", 32, 32), ("bf16", 32, 8)])
@@ -134,7 +139,6 @@ def test_decode_ignores_rows_past_seq_len_and_handles_empty_sequences(torch, dty
     say(f"decode poisoned tails dtype={dtype}")
     seq = [0, 1, 7, 16, 0, 250, 257, 17]
     got, want = _decode_case(torch, seq, hq, hkv, dtype, seed=32, poison=True, min_row_len=40)
-    assert within_tolerance(got, want, dtype)
     assert (got[0] == 0).all() and (got[4] == 0).all()
 
 
@@ -165,7 +169,6 @@ def test_decode_many_short_sequences(torch, n, hq, hkv, dtype):
     got, want = _decode_case(torch, seq, hq, hkv, dtype, seed=n + 1)
     err = np.abs(got - want).max()
     say(f"  max abs err {err:.3e}")
-    assert within_tolerance(got, want, dtype)
     assert (got[seq == 0] == 0).all()
 
 
@@ -182,7 +185,6 @@ def test_decode_batch_sizes_around_the_in_kernel_planning_limits(torch, n):
     got, want = _decode_case(torch, seq, 8, 2, "f16", seed=7100 + n)
     err = np.abs(got - want).max()
     say(f"  max abs err {err:.3e}")
-    assert within_tolerance(got, want, "f16")
     assert (got[seq == 0] == 0).all()
 
 
@@ -204,69 +206,41 @@ def test_decode_single_key_and_identical_keys(torch):
     assert np.abs(got[1] - vals.mean(axis=1)).max() <= 1e-3
 
 
-@pytest.mark.parametrize("cfg", [1, 2])
-def test_decode_small_configs_elementwise(torch, cfg):
-    say(f"decode config {cfg} (every output element)")
+def _params_pair(st, scale=SCALE):
+    sh = st.batch.shape
+    mk = lambda out: vtc.make_params(sh.num_q_heads, sh.num_kv_heads, 128, 16, st.max_blocks_per_seq, sh.dtype, scale, out)
+    return mk(None), mk("f32")
+
+
+@pytest.mark.parametrize("cfg", [1, 2, 3, 4, 5])
+def test_decode_configs_every_element(torch, cfg):
+    # all five configurations at full size, in the launch configuration the benchmark times (caller-held
+    # workspace), every output element against the oracle, with the flat tolerance on both output formats
+    say(f"decode config {cfg}: every output element")
     b = make_step_batch(cfg)
-    st = make_device_step(b, host_random=True)
+    st = make_device_step(b, host_random=cfg <= 2)
     sh = b.shape
-    p = vtc.make_params(sh.num_q_heads, sh.num_kv_heads, 128, 16, st.max_blocks_per_seq, sh.dtype, SCALE)
-    out = vtc.vtc_attn_decode(p, st.q, st.k_cache, st.v_cache, st.block_table, st.seq_lens)
+    p16, p32 = _params_pair(st)
+    ws = torch.empty(vtc.vtc_attn_workspace_bytes(p16, b.num_decode, 0), dtype=torch.uint8, device="cuda")
+    out16 = torch.full_like(st.q, float("nan"))
+    out32 = torch.full(st.q.shape, float("nan"), dtype=torch.float32, device="cuda")
+    vtc.vtc_attn_decode(p16, st.q, st.k_cache, st.v_cache, st.block_table, st.seq_lens, out=out16, workspace=ws)
+    vtc.vtc_attn_decode(p32, st.q, st.k_cache, st.v_cache, st.block_table, st.seq_lens, out=out32, workspace=ws)
     torch.cuda.synchronize()
-    got = OA.widen(tensor_to_bits(out), sh.dtype)
-    want = OA.paged_decode(tensor_to_bits(st.q), tensor_to_bits(st.k_cache), tensor_to_bits(st.v_cache),
-                           st.block_table.cpu().numpy(), b.seq_lens, SCALE, sh.dtype)
-    err = np.abs(got - want).max()
-    say(f"  max abs err {err:.3e}")
-    assert within_tolerance(got, want, sh.dtype)
-
-
-def _sampled_decode_check(torch, st, out, n_samples, seed):
-    b = st.batch
-    sh = b.shape
-    rng = np.random.default_rng(seed)
-    order = np.argsort(b.seq_lens)
-    picks = list(order[:2]) + list(order[-2:]) + list(rng.choice(b.num_decode, size=n_samples, replace=False))
-    q_bits = tensor_to_bits(st.q)
-    got = OA.widen(tensor_to_bits(out), sh.dtype)
-    group = sh.num_q_heads // sh.num_kv_heads
-    worst = 0.0
-    for r in picks:
-        r = int(r)
-        h = int(rng.integers(0, sh.num_q_heads))
-        g = h // group
-        s = int(b.seq_lens[r])
-        keys = OA.widen(sequence_rows_to_host(st.k_cache, st.block_table[r], s, g), sh.dtype)
-        vals = OA.widen(sequence_rows_to_host(st.v_cache, st.block_table[r], s, g), sh.dtype)
-        want = OA.attend_one(OA.widen(q_bits[r, h], sh.dtype), keys, vals, SCALE)
-        worst = max(worst, float(np.abs(got[r, h] - want).max()))
-    return worst, got
-
-
-@pytest.mark.parametrize("cfg", [3, 4, 5])
-def test_decode_full_size_configs_on_sampled_rows(torch, cfg):
-    say(f"decode config {cfg} at full size (sampled rows, bench launch configuration)")
-    b = make_step_batch(cfg)
-    st = make_device_step(b)
-    sh = b.shape
-    p = vtc.make_params(sh.num_q_heads, sh.num_kv_heads, 128, 16, st.max_blocks_per_seq, sh.dtype, SCALE)
-    ws = torch.empty(vtc.vtc_attn_workspace_bytes(p, b.num_decode, 0), dtype=torch.uint8, device="cuda")
-    out = torch.full_like(st.q, float("nan"))
-    vtc.vtc_attn_decode(p, st.q, st.k_cache, st.v_cache, st.block_table, st.seq_lens, out=out, workspace=ws)
-    torch.cuda.synchronize()
-    worst, got = _sampled_decode_check(torch, st, out, n_samples=20, seed=cfg)
-    say(f"  worst sampled max abs err {worst:.3e}")
-    assert np.isfinite(got).all()               # every row was written
-    assert worst <= TOL[sh.dtype]
+    want = full_decode_oracle(st, SCALE)
+    say(f"  {want.shape[0]} requests x {want.shape[1]} heads, {int(b.seq_lens.sum())} context tokens, "
+        f"max |o| {np.abs(want).max():.3f}")
+    check_both_outputs(out16, out32, want, sh.dtype, f"cfg{cfg} decode", flat_only=True)
     # a second call into the same workspace gives the same bits (no stale state, deterministic order)
     out2 = torch.empty_like(st.q)
-    vtc.vtc_attn_decode(p, st.q, st.k_cache, st.v_cache, st.block_table, st.seq_lens, out=out2, workspace=ws)
+    vtc.vtc_attn_decode(p16, st.q, st.k_cache, st.v_cache, st.block_table, st.seq_lens, out=out2, workspace=ws)
     torch.cuda.synchronize()
-    assert torch.equal(out.view(torch.int16), out2.view(torch.int16))
+    assert torch.equal(out16.view(torch.int16), out2.view(torch.int16))
 
 
 # ------------------------------------------------------------------- prefill
-def _prefill_case(torch, q_lens, seq_lens, hq, hkv, dtype, seed, poison=False, scale=SCALE):
+def _prefill_case(torch, q_lens, seq_lens, hq, hkv, dtype, seed, poison=False, scale=SCALE, label="prefill"):
+    """One prefill-chunk call with 16-bit and one with fp32 output rows, both checked against the oracle."""
     rng = np.random.default_rng(seed)
     table, nb = make_block_table(rng, seq_lens, 16)
     cu = np.concatenate([[0], np.cumsum(q_lens)]).astype(np.int32)
@@ -274,13 +248,13 @@ def _prefill_case(torch, q_lens, seq_lens, hq, hkv, dtype, seed, poison=False, s
     if poison:
         poison_unused_rows(k, table, seq_lens, NAN_BITS[dtype])
         poison_unused_rows(v, table, seq_lens, NAN_BITS[dtype])
-    p = vtc.make_params(hq, hkv, 128, 16, table.shape[1], dtype, scale)
-    out = vtc.vtc_attn_prefill_chunk(p, bits_to_tensor(q, dtype), _i32(torch, cu), int(max(q_lens)),
-                                     bits_to_tensor(k, dtype), bits_to_tensor(v, dtype), _i32(torch, table),
-                                     _i32(torch, seq_lens))
+    args = (bits_to_tensor(q, dtype), _i32(torch, cu), int(max(q_lens)), bits_to_tensor(k, dtype),
+            bits_to_tensor(v, dtype), _i32(torch, table), _i32(torch, seq_lens))
+    out16 = vtc.vtc_attn_prefill_chunk(vtc.make_params(hq, hkv, 128, 16, table.shape[1], dtype, scale), *args)
+    out32 = vtc.vtc_attn_prefill_chunk(vtc.make_params(hq, hkv, 128, 16, table.shape[1], dtype, scale, "f32"), *args)
     torch.cuda.synchronize()
-    got = OA.widen(tensor_to_bits(out), dtype)
     want = OA.paged_prefill_chunk(q, cu, k, v, table, seq_lens, scale, dtype)
+    got = check_both_outputs(out16, out32, want, dtype, label)
     return got, want
 
 
@@ -294,7 +268,6 @@ def test_prefill_chunk_ragged_matches_the_oracle(torch, dtype, hq, hkv):
     got, want = _prefill_case(torch, PF_Q, PF_S, hq, hkv, dtype, seed=41, poison=True)
     err = np.abs(got - want)
     say(f"  max abs err {err.max():.3e}  max |o| {np.abs(want).max():.3f}")
-    assert within_tolerance(got, want, dtype)
 
 
 @pytest.mark.parametrize("scale", [-0.07, 0.0, 0.4])
@@ -305,10 +278,8 @@ def test_negative_zero_and_large_scales(torch, scale, dtype, hq, hkv):
     say(f"scale {scale} dtype={dtype} Hq={hq} Hkv={hkv}")
     got, want = _decode_case(torch, [1, 17, 100, 300, 0, 64], hq, hkv, dtype, seed=51, scale=scale)
     say(f"  decode max abs err {np.abs(got - want).max():.3e}")
-    assert within_tolerance(got, want, dtype)
     got, want = _prefill_case(torch, [5, 70, 33], [5, 150, 33], hq, hkv, dtype, seed=52, scale=scale)
     say(f"  prefill max abs err {np.abs(got - want).max():.3e}")
-    assert within_tolerance(got, want, dtype)
 
 
 def test_decode_at_the_capacity_of_the_block_table(torch):
@@ -319,52 +290,68 @@ def test_decode_at_the_capacity_of_the_block_table(torch):
     table, nb = make_block_table(rng, [cap, cap, 7], 16)
     assert table.shape[1] == 5
     q, k, v = make_qkv_numpy(rng, 3, 8, 2, 128, nb, 16, "f16")
-    p = vtc.make_params(8, 2, 128, 16, 5, "f16", SCALE)
-    out = vtc.vtc_attn_decode(p, bits_to_tensor(q, "f16"), bits_to_tensor(k, "f16"), bits_to_tensor(v, "f16"),
-                              _i32(torch, table), _i32(torch, [cap, cap + 1000, 7]))
+    args = (bits_to_tensor(q, "f16"), bits_to_tensor(k, "f16"), bits_to_tensor(v, "f16"), _i32(torch, table),
+            _i32(torch, [cap, cap + 1000, 7]))
+    out16 = vtc.vtc_attn_decode(vtc.make_params(8, 2, 128, 16, 5, "f16", SCALE), *args)
+    out32 = vtc.vtc_attn_decode(vtc.make_params(8, 2, 128, 16, 5, "f16", SCALE, "f32"), *args)
     torch.cuda.synchronize()
     want = OA.paged_decode(q, k, v, table, [cap, cap, 7], SCALE, "f16")
-    assert within_tolerance(OA.widen(tensor_to_bits(out), "f16"), want, "f16")
+    check_both_outputs(out16, out32, want, "f16", "decode at capacity")
 
 
 @pytest.mark.parametrize("chunk", [0, 1])
-def test_prefill_config5_chunks_on_sampled_rows_and_decode_consistency(torch, chunk):
-    say(f"prefill config 5 chunk {chunk} at full size")
+def test_prefill_config5_chunks_every_element_and_decode_consistency(torch, chunk):
+    say(f"prefill config 5 chunk {chunk}: every output element")
     b = make_step_batch(5, prefill_chunk=chunk)
     st = make_device_step(b)
     sh = b.shape
-    p = vtc.make_params(sh.num_q_heads, sh.num_kv_heads, 128, 16, st.max_blocks_per_seq, sh.dtype, SCALE)
-    out = torch.full_like(st.pf_q, float("nan"))
-    vtc.vtc_attn_prefill_chunk(p, st.pf_q, st.pf_cu_q_lens, st.pf_max_q_len, st.k_cache, st.v_cache,
-                               st.pf_block_table, st.pf_seq_lens, out=out)
+    p16, p32 = _params_pair(st)
+    out16 = torch.full_like(st.pf_q, float("nan"))
+    out32 = torch.full(st.pf_q.shape, float("nan"), dtype=torch.float32, device="cuda")
+    for p, out in ((p16, out16), (p32, out32)):
+        vtc.vtc_attn_prefill_chunk(p, st.pf_q, st.pf_cu_q_lens, st.pf_max_q_len, st.k_cache, st.v_cache,
+                                   st.pf_block_table, st.pf_seq_lens, out=out)
     torch.cuda.synchronize()
-    got = OA.widen(tensor_to_bits(out), sh.dtype)
-    assert np.isfinite(got).all()
-    rng = np.random.default_rng(50 + chunk)
-    q_bits = tensor_to_bits(st.pf_q)
-    cu = st.pf_cu_q_lens.cpu().numpy()
-    worst = 0.0
-    for _ in range(24):
-        r = int(rng.integers(0, b.num_prefill))
-        i = int(rng.choice([0, 1, 255, int(rng.integers(0, 256))]))
-        h = int(rng.integers(0, sh.num_q_heads))
-        g = h // (sh.num_q_heads // sh.num_kv_heads)
-        s = int(b.pf_seq_lens[r])
-        pos = s - int(b.pf_q_lens[r]) + i
-        keys = OA.widen(sequence_rows_to_host(st.k_cache, st.pf_block_table[r], pos + 1, g), sh.dtype)
-        vals = OA.widen(sequence_rows_to_host(st.v_cache, st.pf_block_table[r], pos + 1, g), sh.dtype)
-        want = OA.attend_one(OA.widen(q_bits[cu[r] + i, h], sh.dtype), keys, vals, SCALE)
-        worst = max(worst, float(np.abs(got[cu[r] + i, h] - want).max()))
-    say(f"  worst sampled max abs err {worst:.3e}")
-    assert worst <= TOL[sh.dtype]
+    want = full_prefill_oracle(st, SCALE)
+    say(f"  {want.shape[0]} chunk tokens x {want.shape[1]} heads, max |o| {np.abs(want).max():.3f}")
+    # a chunk token early in a first chunk sees only a few keys, so |o| >= 4 does occur here (chunk 0 only)
+    check_both_outputs(out16, out32, want, sh.dtype, f"cfg5 prefill chunk {chunk}", flat_only=chunk == 1)
     # the last chunk token attends to the whole context: same answer as a decode call at that length
     last_rows = (st.pf_cu_q_lens[1:] - 1).long()
     q_last = st.pf_q[last_rows].contiguous()
-    dec = vtc.vtc_attn_decode(p, q_last, st.k_cache, st.v_cache, st.pf_block_table, st.pf_seq_lens)
+    dec = vtc.vtc_attn_decode(p32, q_last, st.k_cache, st.v_cache, st.pf_block_table, st.pf_seq_lens)
     torch.cuda.synchronize()
-    diff = (dec.double() - out[last_rows].double()).abs().max().item()
-    say(f"  prefill last row vs decode: {diff:.3e}")
-    assert diff <= 2 * TOL[sh.dtype]
+    diff = (dec.double() - out32[last_rows].double()).abs().max().item()
+    say(f"  prefill last row vs decode (fp32 rows): {diff:.3e}")
+    assert diff <= 1e-3
+
+
+@pytest.mark.parametrize("dtype,hq,hkv", [("bf16", 8, 2), ("f16", 4, 4)])
+def test_prefill_chunk_longer_than_its_context_gives_zero_rows(torch, dtype, hq, hkv):
+    # seq_lens[r] < chunk length (0 included) is a caller slip with a stated outcome: zero rows for that sequence,
+    # and its block-table row -- here filled with an id far outside the cache -- is never followed
+    say(f"prefill with inconsistent sequences dtype={dtype} Hq={hq} Hkv={hkv}")
+    rng = np.random.default_rng(77)
+    q_lens = [40, 33, 5, 100, 64]
+    seq = [40, 20, 0, 99, 200]
+    table, nb = make_block_table(rng, seq, 16, pad_value=1 << 30)
+    table[1, :] = 1 << 30
+    table[3, :] = 1 << 30
+    cu = np.concatenate([[0], np.cumsum(q_lens)]).astype(np.int32)
+    q, k, v = make_qkv_numpy(rng, int(cu[-1]), hq, hkv, 128, nb, 16, dtype)
+    args = (bits_to_tensor(q, dtype), _i32(torch, cu), max(q_lens), bits_to_tensor(k, dtype), bits_to_tensor(v, dtype),
+            _i32(torch, table), _i32(torch, seq))
+    out16 = vtc.vtc_attn_prefill_chunk(vtc.make_params(hq, hkv, 128, 16, table.shape[1], dtype, SCALE), *args,
+                                       out=torch.full((int(cu[-1]), hq, 128), float("nan"), device="cuda",
+                                                      dtype=torch.float16 if dtype == "f16" else torch.bfloat16))
+    out32 = vtc.vtc_attn_prefill_chunk(vtc.make_params(hq, hkv, 128, 16, table.shape[1], dtype, SCALE, "f32"), *args,
+                                       out=torch.full((int(cu[-1]), hq, 128), float("nan"), device="cuda"))
+    torch.cuda.synchronize()
+    want = OA.paged_prefill_chunk(q, cu, k, v, table, seq, SCALE, dtype)
+    got = check_both_outputs(out16, out32, want, dtype, "prefill, inconsistent sequences")
+    for r in (1, 2, 3):
+        assert (got[cu[r]:cu[r + 1]] == 0).all()
+    assert np.abs(got[:40]).sum() > 0 and np.abs(got[cu[4]:]).sum() > 0
 
 
 def test_prefill_chunking_is_invisible_on_the_gpu(torch):
@@ -388,7 +375,10 @@ def test_prefill_chunking_is_invisible_on_the_gpu(torch):
     assert torch.equal(whole[:first].view(torch.int16), part0.view(torch.int16))
     assert torch.equal(whole[first:].view(torch.int16), part1.view(torch.int16))
     want = OA.paged_prefill_chunk(q, [0, total], k, v, table, [total], SCALE, dtype)
-    assert within_tolerance(OA.widen(tensor_to_bits(whole), dtype), want, dtype)
+    whole32 = vtc.vtc_attn_prefill_chunk(vtc.make_params(hq, hkv, 128, 16, table.shape[1], dtype, SCALE, "f32"), qd,
+                                         _i32(torch, [0, total]), total, kd, vd, td, _i32(torch, [total]))
+    torch.cuda.synchronize()
+    check_both_outputs(whole, whole32, want, dtype, "prefill in one chunk")
 
 
 # ----------------------------------------------------------- extreme logits
@@ -406,23 +396,23 @@ def test_peaked_softmax_with_large_logits(torch, dtype, hq, hkv):
     poison_unused_rows(k, table, seq, NAN_BITS[dtype])
     poison_unused_rows(v, table, seq, NAN_BITS[dtype])
     p = vtc.make_params(hq, hkv, 128, 16, table.shape[1], dtype, SCALE)
+    p32 = vtc.make_params(hq, hkv, 128, 16, table.shape[1], dtype, SCALE, "f32")
     kd, vd, td = bits_to_tensor(k, dtype), bits_to_tensor(v, dtype), _i32(torch, table)
     out = vtc.vtc_attn_decode(p, bits_to_tensor(q, dtype), kd, vd, td, _i32(torch, seq))
+    out32 = vtc.vtc_attn_decode(p32, bits_to_tensor(q, dtype), kd, vd, td, _i32(torch, seq))
     torch.cuda.synchronize()
     want = OA.paged_decode(q, k, v, table, seq, SCALE, dtype)
-    got = OA.widen(tensor_to_bits(out), dtype)
-    say(f"  decode max abs err {np.abs(got - want).max():.3e}  largest weight {max(OA.softmax_weights(OA.widen(q[3, 0], dtype), OA.gather_sequence(k, table[3], 300, 0, dtype), SCALE)):.3f}")
-    assert within_tolerance(got, want, dtype)
+    say(f"  largest weight {max(OA.softmax_weights(OA.widen(q[3, 0], dtype), OA.gather_sequence(k, table[3], 300, 0, dtype), SCALE)):.3f}")
+    check_both_outputs(out, out32, want, dtype, "decode, peaked softmax")
     # the same cache as one prefill chunk per sequence (whole prompts)
     cu = np.concatenate([[0], np.cumsum(seq)]).astype(np.int32)
     rng2 = np.random.default_rng(62)
     qp = f32_to_storage_bits(rng2.standard_normal((int(cu[-1]), hq, 128), dtype=np.float32), dtype)
     outp = vtc.vtc_attn_prefill_chunk(p, bits_to_tensor(qp, dtype), _i32(torch, cu), max(seq), kd, vd, td, _i32(torch, seq))
+    outp32 = vtc.vtc_attn_prefill_chunk(p32, bits_to_tensor(qp, dtype), _i32(torch, cu), max(seq), kd, vd, td, _i32(torch, seq))
     torch.cuda.synchronize()
     wantp = OA.paged_prefill_chunk(qp, cu, k, v, table, seq, SCALE, dtype)
-    gotp = OA.widen(tensor_to_bits(outp), dtype)
-    say(f"  prefill max abs err {np.abs(gotp - wantp).max():.3e}")
-    assert within_tolerance(gotp, wantp, dtype)
+    check_both_outputs(outp, outp32, wantp, dtype, "prefill, peaked softmax")
 
 
 # ------------------------------------------------------------- random shapes
@@ -433,10 +423,8 @@ def test_contexts_far_beyond_the_workload_lengths(torch, dtype, hq, hkv):
     say(f"long contexts dtype={dtype} Hq={hq} Hkv={hkv}")
     got, want = _decode_case(torch, [65536, 3, 40000, 1, 16], hq, hkv, dtype, seed=83)
     say(f"  decode max abs err {np.abs(got - want).max():.3e}")
-    assert within_tolerance(got, want, dtype)
     got, want = _prefill_case(torch, [100, 7, 33], [30000, 9001, 33], hq, hkv, dtype, seed=84)
     say(f"  prefill max abs err {np.abs(got - want).max():.3e}")
-    assert within_tolerance(got, want, dtype)
 
 
 @pytest.mark.parametrize("seed", range(10))
@@ -455,7 +443,6 @@ def test_decode_and_prefill_on_random_small_shapes(torch, seed):
     got, want = _decode_case(torch, seq, hkv * group, hkv, dtype, seed=9100 + seed, poison=True,
                              min_row_len=int(rng.integers(0, 30)))
     say(f"  decode max abs err {np.abs(got - want).max():.3e}")
-    assert within_tolerance(got, want, dtype)
     assert (got[seq == 0] == 0).all()
     # prefill: chunks of random length ending anywhere in a context of random length
     m = int(rng.integers(1, 6))
@@ -463,7 +450,6 @@ def test_decode_and_prefill_on_random_small_shapes(torch, seed):
     ctx = (q_lens + rng.integers(0, 150, size=m) * rng.integers(0, 2, size=m)).astype(np.int32)
     got, want = _prefill_case(torch, q_lens, ctx, hkv * group, hkv, dtype, seed=9200 + seed, poison=True)
     say(f"  prefill q_lens {q_lens.tolist()} ctx {ctx.tolist()} max abs err {np.abs(got - want).max():.3e}")
-    assert within_tolerance(got, want, dtype)
 
 
 # ---------------------------------------------------------------- whole step
@@ -484,5 +470,6 @@ def test_mixed_step_config5_on_one_stream(torch):
     ids, n_in, n_out = b.counter_update_args()
     assert st.counters.cpu().tolist() == oracle_counter_update(b.counters_before, ids, n_in, n_out, b.w_p, b.w_q)
     assert sum(st.counters.cpu().tolist()) == 1 * 16 * 512 + 2 * 256
-    worst, got = _sampled_decode_check(torch, st, dec, n_samples=8, seed=5)
-    assert worst <= TOL[sh.dtype] and torch.isfinite(pf.float()).all()
+    from tests.helpers import check_storage_output
+    check_storage_output(dec.double().cpu().numpy(), full_decode_oracle(st, SCALE), sh.dtype, "mixed step decode", flat_only=True)
+    check_storage_output(pf.double().cpu().numpy(), full_prefill_oracle(st, SCALE), sh.dtype, "mixed step prefill")

@@ -99,3 +99,13 @@ def test_elementwise_tolerance_is_flat_where_the_output_format_allows_it():
     assert within_tolerance(rounded, exact, "bf16")
     assert not within_tolerance(rounded - np.array([2.0 ** -5, 2.0 ** -6]), exact, "bf16")
     assert not within_tolerance(np.array([np.nan]), np.array([0.0]), "bf16")
+    # the report of how the bound was used: elements the format limits, and elements that needed that allowance
+    from tests.helpers import check_f32_output, check_storage_output, parity_stats
+    st = parity_stats(np.array([4.0, 3.0, 1.0]), np.array([4.0 + 2.0 ** -6 - 1e-6, 3.0 + 2.0 ** -7 - 1e-6, 1.0]), "bf16")
+    assert st == {"max_abs": pytest.approx(2.0 ** -6 - 1e-6), "elements": 3, "format_limited": 1, "over_flat": 1, "ok": True}
+    check_storage_output(np.array([4.0, 1.0]), np.array([4.0 + 2.0 ** -6 - 1e-6, 1.0]), "bf16", "demo")
+    with pytest.raises(AssertionError):            # ... which a benchmark configuration must not need
+        check_storage_output(np.array([4.0, 1.0]), np.array([4.0 + 2.0 ** -6 - 1e-6, 1.0]), "bf16", "demo", flat_only=True)
+    with pytest.raises(AssertionError):            # fp32 rows get the flat bar whatever their magnitude
+        check_f32_output(np.array([4.0]), np.array([4.0 + 2.0 ** -6 - 1e-6]), "bf16", "demo")
+    check_f32_output(np.array([4.0]), np.array([4.0 + 9e-3]), "bf16", "demo")
