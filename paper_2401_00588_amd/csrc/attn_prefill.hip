@@ -170,7 +170,7 @@ __global__ __launch_bounds__(kPfThreads, 2) void prefill_chunk_kernel(
   if (qt * kTokensPerWg >= lq) return;                             // uniform over the workgroup
   if (min(max(s_raw, 0), max_blocks_per_seq * kBlockSize) < lq) {
     // The context is shorter than the chunk that is said to end it: there is no position to give the chunk's
-    // tokens.  Their output rows are zeroed and nothing of the cache or the block table is touched.
+    // tokens.  Their output rows are zeroed and no cache block is read for the sequence.
     const int words_per_row = out_f32 ? kHeadDim : kHeadDim / 2;   // 4-byte words of one (token, head) row
     const int tok_lo = qt * kTokensPerWg, tok_hi = min(lq, tok_lo + kTokensPerWg);
     const int group0 = num_q_heads / num_kv_heads;
