@@ -60,7 +60,9 @@ enum {
                                        out_dtype neither dtype nor VTC_F32,
                                        num_q_heads/num_kv_heads not in {1,2,4,8}          */
   VTC_ERR_WORKSPACE_TOO_SMALL = -3, /* workspace_bytes < vtc_attn_workspace_bytes(...)   */
-  VTC_ERR_HIP = -4                  /* a HIP runtime call or kernel launch failed        */
+  VTC_ERR_HIP = -4,                 /* a HIP runtime call or kernel launch failed        */
+  VTC_ERR_STATIC_LIMIT = -5         /* vtc_attn_decode_static: more sequences than its
+                                       built-in scratch array is laid out for             */
 };
 
 /* Host struct, passed by const pointer; never retained by the library. */
@@ -128,6 +130,27 @@ int vtc_attn_decode(const vtc_attn_params* params /*[host]*/, int32_t num_seqs, 
                     const void* k_cache, const void* v_cache, const int32_t* block_table,
                     const int32_t* seq_lens, void* out, void* workspace, size_t workspace_bytes,
                     void* hip_stream);
+
+/*
+ * vtc_attn_decode for callers that cannot allocate device memory or hand over a
+ * workspace: code under HIP graph capture, tight serving loops, harnesses that
+ * forbid hipMalloc.  Same arguments, results and error behaviour as
+ * vtc_attn_decode, except that the workspace is a 20 MiB device array inside the
+ * library image (every device the library runs on holds its own copy until the
+ * process ends).  The call allocates and frees nothing.
+ *   - num_seqs may be at most 65536; more returns VTC_ERR_STATIC_LIMIT.  20 MiB
+ *     hold the full wave count of a 256-compute-unit device for every supported
+ *     shape; on a larger device the launch uses the waves that fit.
+ *   - Every call on a device shares that device's array: calls that overlap on
+ *     one device (different streams, different threads) race.  Order them on one
+ *     stream.  The array keeps the last call's contents; nothing in it has to be
+ *     cleared between calls.
+ *   - The first call on a device looks up the array's address (a HIP runtime
+ *     query, no allocation); make it outside any stream capture.
+ */
+int vtc_attn_decode_static(const vtc_attn_params* params /*[host]*/, int32_t num_seqs, const void* q,
+                           const void* k_cache, const void* v_cache, const int32_t* block_table,
+                           const int32_t* seq_lens, void* out, void* hip_stream);
 
 /*
  * Measurement hook: exactly vtc_attn_decode, and in addition records the HIP

@@ -17,6 +17,7 @@ from .binding import (  # noqa: F401
     load_library,
     make_params,
     vtc_attn_decode,
+    vtc_attn_decode_static,
     vtc_attn_prefill_chunk,
     vtc_attn_workspace_bytes,
     vtc_counter_update,

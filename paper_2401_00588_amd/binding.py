@@ -72,6 +72,8 @@ def load_library() -> ctypes.CDLL:
     lib.vtc_attn_workspace_bytes.argtypes = [P, i32, i32]
     lib.vtc_attn_decode.restype = ctypes.c_int
     lib.vtc_attn_decode.argtypes = [P, i32, vp, vp, vp, vp, vp, vp, vp, sz, vp]
+    lib.vtc_attn_decode_static.restype = ctypes.c_int
+    lib.vtc_attn_decode_static.argtypes = [P, i32, vp, vp, vp, vp, vp, vp, vp]
     lib.vtc_attn_decode_profiled.restype = ctypes.c_int
     lib.vtc_attn_decode_profiled.argtypes = [P, i32, vp, vp, vp, vp, vp, vp, vp, sz, vp, vp, vp]
     lib.vtc_step_decode.restype = ctypes.c_int
@@ -242,6 +244,34 @@ def vtc_attn_decode(params: AttnParams, q, k_cache, v_cache, block_table, seq_le
                                           ev_end.handle if ev_end else None)
     if rc != 0:
         raise VtcError(rc, "vtc_attn_decode")
+    return out
+
+
+def vtc_attn_decode_static(params: AttnParams, q, k_cache, v_cache, block_table, seq_lens, out):
+    """``vtc_attn_decode`` on the library's built-in scratch array: no workspace argument, and nothing is
+    allocated here either (``out`` must be given)."""
+    torch = _torch()
+    lib = load_library()
+    elt = _elt_dtype(params)
+    _check(q, "q", elt, 3)
+    _check(k_cache, "k_cache", elt, 4)
+    _check(v_cache, "v_cache", elt, 4)
+    _check(block_table, "block_table", torch.int32, 2)
+    _check(seq_lens, "seq_lens", torch.int32, 1)
+    n = int(seq_lens.shape[0])
+    if tuple(q.shape) != (n, params.num_q_heads, params.head_dim):
+        raise ValueError("q must be [num_seqs, num_q_heads, head_dim]")
+    if tuple(k_cache.shape[1:]) != (params.num_kv_heads, params.block_size, params.head_dim) or k_cache.shape != v_cache.shape:
+        raise ValueError("k_cache / v_cache must be [num_blocks, num_kv_heads, block_size, head_dim]")
+    if tuple(block_table.shape) != (n, params.max_blocks_per_seq):
+        raise ValueError("block_table must be [num_seqs, max_blocks_per_seq]")
+    _check(out, "out", _out_dtype(params), 3)
+    if out.shape != q.shape:
+        raise ValueError("out must have the shape of q")
+    rc = lib.vtc_attn_decode_static(ctypes.byref(params), n, q.data_ptr(), k_cache.data_ptr(), v_cache.data_ptr(),
+                                    block_table.data_ptr(), seq_lens.data_ptr(), out.data_ptr(), _stream())
+    if rc != 0:
+        raise VtcError(rc, "vtc_attn_decode_static")
     return out
 
 

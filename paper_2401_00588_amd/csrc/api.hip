@@ -35,6 +35,8 @@ const char* vtc_strerror(int code) {
              "num_q_heads/num_kv_heads in {1,2,4,8})";
     case VTC_ERR_WORKSPACE_TOO_SMALL: return "workspace smaller than vtc_attn_workspace_bytes()";
     case VTC_ERR_HIP: return "HIP runtime error (launch failed or no usable device)";
+    case VTC_ERR_STATIC_LIMIT:
+      return "more sequences than vtc_attn_decode_static's built-in scratch array is laid out for (65536)";
     default: return "unknown error code";
   }
 }

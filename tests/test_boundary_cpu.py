@@ -191,3 +191,22 @@ def test_fused_step_validates_both_halves_before_enqueueing(lib):
                                1, 2, None, 0, None) == 0
     assert lib.vtc_step_decode(ctypes.byref(p), 0, None, None, None, None, None, None, None, 0, a, a, a, 5,
                                1, 2, None, 0, None) == 0   # no clients: every id is out of range
+
+
+def test_static_decode_validates_on_the_host(lib):
+    # the entry point without a workspace argument: same host-side checks, plus its own size limit, all before
+    # any HIP call
+    p = good_params()
+    a = ctypes.c_void_p(4096)
+    call = lambda n, args: lib.vtc_attn_decode_static(ctypes.byref(p), n, *args, None)
+    assert call(0, [None] * 6) == 0
+    assert call(-1, [a] * 6) == -1
+    assert call(65537, [a] * 6) == -5
+    assert vtc.vtc_strerror(-5) and "65536" in vtc.vtc_strerror(-5)
+    for hole in range(6):
+        args = [a] * 6
+        args[hole] = None
+        assert call(4, args) == -1
+    assert call(4, [ctypes.c_void_p(4098)] + [a] * 5) == -1
+    bad = good_params(head_dim=64)
+    assert lib.vtc_attn_decode_static(ctypes.byref(bad), 4, a, a, a, a, a, a, None) == -2
