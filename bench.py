@@ -1,7 +1,8 @@
 #!/usr/bin/env python3
 """Benchmark of one VTC serving step on one MI355X.
 
-    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload cfg3|cfg4|cfg5] [--no-cpu-baseline]
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload cfg2|cfg3|cfg4|cfg5] [--no-cpu-baseline]
+                    [--no-other-configs]
 
 A step is one pass of the hot path over one synthetic batch that is already
 resident in HBM: decode attention over the paged KV cache of every running
@@ -11,6 +12,9 @@ batch (carried by the decode call's last launch: ``vtc_step_decode``).  Prints O
 roofline of the dominant kernel (decode attention, HBM-bound; its duration is
 measured with HIP events recorded on the launch stream right around that
 kernel) and the CPU oracle timed on a bounded sample of the same workload.
+Unless --no-other-configs is given, the line also carries, under
+"other_configs", the decode kernel on the other configurations and the
+prefill-chunk kernel on both chunks of cfg5 (a second or two in all).
 """
 from __future__ import annotations
 
@@ -55,6 +59,8 @@ def parse_args():
     ap.add_argument("--workload", default="cfg3", choices=["cfg2", "cfg3", "cfg4", "cfg5"])
     ap.add_argument("--prefill-chunk", type=int, default=1, choices=[0, 1], help="cfg5: which 256-token chunk")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-other-configs", action="store_true",
+                    help="skip the short runs of the other configurations (key other_configs)")
     ap.add_argument("--cpu-sample-requests", type=int, default=256,
                     help="decode requests handed to the CPU oracle (default: the whole cfg3 batch, ~20 core-seconds)")
     ap.add_argument("--calibrate-copy", action="store_true",
@@ -183,6 +189,97 @@ def aux_kernel_times(torch, vtc, st, params, stream, reps: int = 50):
                                                                                    b.w_q)),
         "note": "back-to-back launches on one stream, average per launch",
     }
+
+
+def decode_kernel_on(torch, vtc, cfg, steps=20, warmup=5):
+    """Decode kernel time on configuration ``cfg``: a short run of whole decode steps with a HIP event pair around
+    the attention kernel on every 4th step (rotating over copies of a small cache, as in the main run)."""
+    from workloads import make_device_step, make_step_batch
+
+    batch = make_step_batch(cfg)
+    st = make_device_step(batch)
+    sh = batch.shape
+    params = vtc.make_params(sh.num_q_heads, sh.num_kv_heads, sh.head_dim, sh.block_size, st.max_blocks_per_seq,
+                             sh.dtype, 1.0 / math.sqrt(sh.head_dim))
+    ws = torch.empty(vtc.vtc_attn_workspace_bytes(params, batch.num_decode, 0), dtype=torch.uint8, device="cuda")
+    out = torch.empty_like(st.q)
+    cache_bytes = 2 * st.k_cache.numel() * st.k_cache.element_size()
+    n_copies = 1 if cache_bytes >= (1 << 30) else min(16, -(-(2 << 30) // cache_bytes))
+    ks = [st.k_cache] + [st.k_cache.clone() for _ in range(n_copies - 1)]
+    vs = [st.v_cache] + [st.v_cache.clone() for _ in range(n_copies - 1)]
+    stream = torch.cuda.Stream()
+    timed = [i for i in range(steps) if i % 4 == 0]
+    evs = {i: (vtc.HipEvent(), vtc.HipEvent()) for i in timed}
+    with torch.cuda.stream(stream):
+        for i in range(-warmup, steps):
+            eb, ee = evs.get(i, (None, None))
+            vtc.vtc_step_decode(params, st.q, ks[i % n_copies], vs[i % n_copies], st.block_table, st.seq_lens,
+                                st.counters, st.cu_client_ids[:batch.num_decode].contiguous(), None,
+                                st.cu_n_out[:batch.num_decode].contiguous(), batch.w_p, batch.w_q, out=out,
+                                workspace=ws, ev_begin=eb, ev_end=ee)
+            if i == -1:
+                torch.cuda.synchronize()
+                t0 = time.perf_counter()
+        torch.cuda.synchronize()
+        step_ms = (time.perf_counter() - t0) * 1e3 / steps
+    ms = sorted(a.elapsed_ms(b) for a, b in evs.values())
+    avg = sum(ms) / len(ms)
+    kv = batch.decode_kv_bytes
+    return {"kernel": "decode_attend_kernel", "requests": batch.num_decode, "kv_bytes": kv, "dtype": sh.dtype,
+            "kernel_avg_ms": round(avg, 5), "kernel_min_ms": round(ms[0], 5), "achieved": round(kv / avg / 1e6, 1),
+            "unit": "GB/s", "frac": round(kv / avg / 1e6 / HBM_PEAK_GBS, 4), "step_ms": round(step_ms, 5),
+            "kv_cache_copies": n_copies}
+
+
+def prefill_kernel_on_cfg5(torch, vtc, chunk, launches=24, reps=5, rotate=6):
+    """Prefill-chunk kernel time on chunk ``chunk`` of cfg5 (16 prompts x 256 chunk tokens, GQA 32/8 bf16): ``launches``
+    back-to-back launches between one event pair, over ``rotate`` distinct sets of inputs and outputs (q, out and
+    the paged cache: ~100 MB each, more than the last-level cache in all), so that every launch streams from HBM and
+    no event sits between two kernels.  Average time per launch, median over ``reps`` such runs."""
+    import numpy as np
+
+    from workloads import make_block_table, make_step_batch
+
+    batch = make_step_batch(5, prefill_chunk=chunk)
+    sh = batch.shape
+    n, lq, s_len = batch.num_prefill, int(batch.pf_q_lens[0]), int(batch.pf_seq_lens[0])
+    sets = []
+    for i in range(rotate):
+        table, nb = make_block_table(np.random.default_rng(500 + 10 * chunk + i), [s_len] * n, sh.block_size)
+        gen = torch.Generator(device="cuda")
+        gen.manual_seed(500 + 10 * chunk + i)
+        mk = lambda *shape: torch.randn(shape, generator=gen, device="cuda", dtype=torch.float32).to(torch.bfloat16)
+        sets.append((mk(n * lq, sh.num_q_heads, sh.head_dim), mk(nb, sh.num_kv_heads, sh.block_size, sh.head_dim),
+                     mk(nb, sh.num_kv_heads, sh.block_size, sh.head_dim), torch.from_numpy(table).cuda(),
+                     torch.empty((n * lq, sh.num_q_heads, sh.head_dim), dtype=torch.bfloat16, device="cuda")))
+    cu = torch.arange(0, n * lq + 1, lq, dtype=torch.int32, device="cuda")
+    seq = torch.full((n,), s_len, dtype=torch.int32, device="cuda")
+    params = vtc.make_params(sh.num_q_heads, sh.num_kv_heads, sh.head_dim, sh.block_size, sets[0][3].shape[1], sh.dtype,
+                             1.0 / math.sqrt(sh.head_dim))
+
+    def launch(i):
+        q, k, v, table, out = sets[i % rotate]
+        vtc.vtc_attn_prefill_chunk(params, q, cu, lq, k, v, table, seq, out=out)
+
+    for i in range(rotate):
+        launch(i)
+    torch.cuda.synchronize()
+    per_launch = []
+    for _ in range(reps):
+        a, e = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        a.record()
+        for i in range(launches):
+            launch(i)
+        e.record()
+        e.synchronize()
+        per_launch.append(a.elapsed_time(e) / launches)
+    per_launch.sort()
+    ms = per_launch[len(per_launch) // 2]
+    tf = batch.prefill_flops / ms / 1e9
+    return {"kernel": "prefill_chunk_kernel", "chunk": chunk, "flops": batch.prefill_flops, "dtype": sh.dtype,
+            "ms_per_launch": round(ms, 5), "ms_per_launch_min": round(per_launch[0], 5), "achieved": round(tf, 1),
+            "unit": "TFLOP/s", "frac": round(tf / MFMA_PEAK_TFLOPS, 4),
+            "method": f"{launches} back-to-back launches over {rotate} distinct input sets per event pair"}
 
 
 def main() -> int:
@@ -323,12 +420,26 @@ def main() -> int:
             "peak": MFMA_PEAK_TFLOPS,
             "unit": "TFLOP/s",
             "frac": round(batch.prefill_flops / (pf_avg * 1e-3) / 1e12 / MFMA_PEAK_TFLOPS, 4),
+            "note": "one launch between two events inside the mixed step (the events add a few us); "
+                    "other_configs holds the back-to-back figure",
         }
     line["aux_kernels_us"] = aux_kernel_times(torch, vtc, st, params, stream)
     if not args.no_cpu_baseline:
         line["cpu_baseline"] = cpu_baseline(st, scale, args.cpu_sample_requests)
         line["cpu_baseline"]["value"] = round(line["cpu_baseline"]["value"], 4)
         line["cpu_baseline"]["seconds"] = round(line["cpu_baseline"]["seconds"], 3)
+    if not args.no_other_configs:
+        st = k_copies = v_copies = out = pf_out = ws = None            # free the main workload's memory first
+        torch.cuda.empty_cache()
+        others = {}
+        for c in (2, 3, 4, 5):
+            if c != cfg:
+                others[f"cfg{c}_decode"] = decode_kernel_on(torch, vtc, c)
+                torch.cuda.empty_cache()
+        for chunk in (0, 1):
+            others[f"cfg5_prefill_chunk{chunk}"] = prefill_kernel_on_cfg5(torch, vtc, chunk)
+            torch.cuda.empty_cache()
+        line["other_configs"] = others
     print(json.dumps(line), flush=True)
     return 0
 

@@ -83,7 +83,7 @@ class LastFivePredictor:
 class StepRecord:
     iteration: int
     time_s: float
-    admitted: List[Running]                 # B_new of this iteration (generated == 0 at admission)
+    admitted: List[Running]                 # the minibatch of this iteration (generated == 0 at admission)
     decode_rids: List[int]
     decode_clients: List[int]
     decode_n_input: List[int]
@@ -142,62 +142,71 @@ class VTCScheduler:
         return self.reserved + minibatch_reserved + req.n_input + self.L_output <= self.M
 
     # ---------------------------------------------------- monitoring stream
+    def _lifted_counter(self, client: int) -> int:
+        """Counter a client gets when a request of it arrives while none of its requests is waiting: not below
+        the smallest counter among the clients that are waiting, or -- nobody waiting at all -- not below the
+        counter of the client whose queue emptied last (Algorithm 2, monitoring stream)."""
+        waiting = self.waiting_clients()
+        if waiting:
+            floor = min(self.c[i] for i in waiting)
+        elif self.last_left is not None:
+            floor = self.c[self.last_left]
+        else:
+            return self.c[client]                       # nobody has ever left the queue: nothing to catch up with
+        return max(self.c[client], floor)
+
     def on_arrival(self, req) -> None:
-        u = req.client
-        if not self.Q[u]:                                   # u has no request waiting
-            if self.lift:
-                P = self.waiting_clients()
-                if not P:                                   # the whole queue is empty
-                    if self.last_left is not None:
-                        self.c[u] = max(self.c[u], self.c[self.last_left])
-                else:
-                    self.c[u] = max(self.c[u], min(self.c[i] for i in P))
-        self.Q[u].append(req)
+        if self.lift and not self.Q[req.client]:
+            self.c[req.client] = self._lifted_counter(req.client)
+        self.Q[req.client].append(req)
         self._notify("arrival")
 
     # ----------------------------------------------------- execution stream
+    def _admission_charge(self, run: Running, req) -> None:
+        """What a client pays when its request enters the minibatch (Algorithm 2; Section 4.2; Algorithm 3)."""
+        client = req.client
+        if self.cost is not None:
+            self.c[client] += self.cost(req.n_input, 0)
+            self.service[client] += self.cost(req.n_input, 0)
+            return
+        self.c[client] += self.w_p * req.n_input
+        self.service[client] += self.w_p * req.n_input
+        if self.predictor is not None:
+            run.predicted = int(self.predictor(client, req))
+            self.c[client] += self.w_q * run.predicted      # pre-payment; not service received yet
+
     def select_new_requests(self) -> List[Running]:
-        B_new: List[Running] = []
-        new_reserved = 0
-        while True:
-            P = self.waiting_clients()
-            if not P:
+        admitted: List[Running] = []
+        admitted_reserved = 0
+        # keep taking the oldest request of the waiting client with the smallest counter until it does not fit
+        while self.waiting_clients():
+            lowest = min(self.waiting_clients(), key=lambda i: (self.c[i], i))
+            head = self.Q[lowest][0]
+            if not self._fits(head, admitted, admitted_reserved):
                 break
-            k = min(P, key=lambda i: (self.c[i], i))
-            r = self.Q[k][0]                                # earliest request of k
-            if not self._fits(r, B_new, new_reserved):
-                break
-            run = Running(r.rid, r.client, r.n_input, r.n_output)
-            if self.cost is not None:
-                self.c[k] += self.cost(r.n_input, 0)
-                self.service[k] += self.cost(r.n_input, 0)
-            else:
-                self.c[k] += self.w_p * r.n_input
-                self.service[k] += self.w_p * r.n_input
-                if self.predictor is not None:
-                    run.predicted = int(self.predictor(k, r))
-                    self.c[k] += self.w_q * run.predicted       # pre-payment; not service received yet
-            B_new.append(run)
-            new_reserved += r.n_input + self.L_output
-            self.Q[k].popleft()
-            if not self.Q[k]:
-                self.last_left = k
+            run = Running(head.rid, head.client, head.n_input, head.n_output)
+            self._admission_charge(run, head)
+            admitted.append(run)
+            admitted_reserved += head.n_input + self.L_output
+            self.Q[lowest].popleft()
+            if not self.Q[lowest]:
+                self.last_left = lowest
             self._notify("admit")
-        self.reserved += new_reserved
-        if not self.B and not B_new and self.waiting_clients():
+        self.reserved += admitted_reserved
+        if not self.B and not admitted and self.waiting_clients():
             raise ValueError("the head request can never fit: input_length + L_output exceeds M")
-        return B_new
+        return admitted
 
     def step(self, time_s: float = 0.0, admit: bool = True) -> StepRecord:
-        B_new = self.select_new_requests() if admit else []
-        # forward_prefill(B_new) happens here on a real server
-        self.B.extend(B_new)
+        admitted = self.select_new_requests() if admit else []
+        # a real server prefills the admitted requests here
+        self.B.extend(admitted)
         # forward_decode(B): every running request produces one token
         before = list(self.c)
         rec = StepRecord(
             iteration=self.iteration,
             time_s=time_s,
-            admitted=B_new,
+            admitted=admitted,
             decode_rids=[x.rid for x in self.B],
             decode_clients=[x.client for x in self.B],
             decode_n_input=[x.n_input for x in self.B],

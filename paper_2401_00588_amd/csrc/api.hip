@@ -6,19 +6,24 @@
 
 namespace vtc {
 
-int device_cu_count() {
+DeviceShape device_shape() {
   static std::mutex mu;
-  static int cached[64];
+  static DeviceShape cached[64];
+  const DeviceShape assumed{256, 8};                     // an MI355X in its default partition mode
   int dev = 0;
-  if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64) return 256;
+  if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64) return assumed;
   std::lock_guard<std::mutex> lock(mu);
-  if (cached[dev] == 0) {
-    int n = 0;
-    if (hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || n <= 0) n = 256;
-    cached[dev] = n;
+  if (cached[dev].cus == 0) {
+    int cus = 0, xcds = 0;
+    if (hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || cus <= 0) cus = assumed.cus;
+    if (hipDeviceGetAttribute(&xcds, hipDeviceAttributeNumberOfXccs, dev) != hipSuccess || xcds <= 0 || cus % xcds != 0)
+      xcds = 1;                                          // unknown: treat the device as one die (plain block order)
+    cached[dev] = DeviceShape{cus, xcds};
   }
   return cached[dev];
 }
+
+int device_cu_count() { return device_shape().cus; }
 
 }  // namespace vtc
 

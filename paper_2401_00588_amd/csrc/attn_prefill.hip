@@ -41,8 +41,6 @@ using u32x2 = uint32_t __attribute__((ext_vector_type(2)));
 
 constexpr int kQkAhead = 6;              // K fragments in flight ahead of the product that uses them
 constexpr int kPvAhead = 4;              // V^T fragments in flight ahead of the product(s) that use them
-constexpr int kXcds = 8;                 // accelerator complex dies of an MI355X
-constexpr int kCusPerXcd = 32;           // compute units on each of them
 constexpr int kPfThreads = 256;
 constexpr int kPfRows = 32;              // query rows per wave
 constexpr int kPfKTile = 64;             // keys per LDS tile
@@ -117,35 +115,35 @@ __global__ __launch_bounds__(kPfThreads, 2) void prefill_chunk_kernel(
     const uint16_t* __restrict__ q, const int32_t* __restrict__ cu_q_lens, const uint16_t* __restrict__ k_cache,
     const uint16_t* __restrict__ v_cache, const int32_t* __restrict__ block_table,
     const int32_t* __restrict__ seq_lens, void* __restrict__ out, int32_t out_f32, int32_t num_q_heads,
-    int32_t num_kv_heads, int32_t max_blocks_per_seq, float scale2) {
+    int32_t num_kv_heads, int32_t max_blocks_per_seq, float scale2, int32_t xcds, int32_t cus_per_xcd) {
   constexpr int TT = 4 / HW;                       // 32-token tiles per workgroup
   constexpr int kTokensPerWg = kPfRows * TT;
   __shared__ __attribute__((aligned(1024))) uint16_t lds[4 * kTileElems64];    // K buffers 0, 1, then V buffers 0, 1
   uint16_t* const k_lds = lds;
   uint16_t* const v_lds = lds + 2 * kTileElems64;
 
-  // Workgroups are dispatched round-robin over the 8 XCDs (each with its own L2) in linear
+  // Workgroups are dispatched round-robin over the device's XCDs (each with its own L2) in linear
   // block order.  All query tiles that read the same K/V -- one (sequence, kv head) -- are
   // placed on one XCD, so that K/V comes out of that XCD's L2 after the first tile's read.
   const int n_qt = gridDim.x;                                      // query tiles per (sequence, head slot)
   const int n_units = gridDim.y * gridDim.z;                       // (head slot, sequence) pairs
   const int linear = blockIdx.x + n_qt * (blockIdx.y + gridDim.y * blockIdx.z);
   int qt, unit;
-  if (n_units % kXcds == 0) {
-    const int per_xcd = n_units / kXcds;
-    const int j = linear / kXcds;
+  if (xcds > 1 && n_units % xcds == 0) {
+    const int per_xcd = n_units / xcds;
+    const int j = linear / xcds;
     // Units go in groups whose query tiles come to about one workgroup per CU of the XCD, and inside a group the
     // order is query tile first, unit second: the XCD's 4 MB L2 then serves the K/V of a few units at a time, each
     // of them to all its query tiles at once, instead of a slice of every unit's K/V in every round of workgroups.
     // (Measured on 16 units x 8 query tiles per XCD: groups of 4 units -7 % on a 256-key chunk, -1.5 % on a
     // 512-key chunk against no grouping; groups of 1, 2, 3 or 8 units are slower than 4.)
-    const int gsz = min(per_xcd, max(1, kCusPerXcd / n_qt));
+    const int gsz = min(per_xcd, max(1, cus_per_xcd / n_qt));
     const int per_group = gsz * n_qt;
     const int grp = j / per_group, jj = j % per_group;
     const int in_grp = min(gsz, per_xcd - grp * gsz);             // the last group may be smaller
-    unit = (grp * gsz + jj % in_grp) * kXcds + linear % kXcds;
+    unit = (grp * gsz + jj % in_grp) * xcds + linear % xcds;
     qt = jj / in_grp;
-  } else {                                                         // odd shapes: plain order
+  } else {                                                         // odd shapes, or one die: plain order
     qt = blockIdx.x;
     unit = blockIdx.y + gridDim.y * blockIdx.z;
   }
@@ -463,11 +461,12 @@ static int launch_hw(const vtc_attn_params& p, int32_t num_seqs, const void* q, 
   dim3 grid((max_q_len + kTokensPerWg - 1) / kTokensPerWg, (unsigned)gy, num_seqs);
   float scale2 = p.scale * kLog2e;
   if (scale2 == 0.f) scale2 = 1e-30f;   // all logits equal either way; keeps (-inf) * scale of masked keys well defined
+  const DeviceShape shape = device_shape();
   auto go = [&](auto kernel) {
     hipLaunchKernelGGL(kernel, grid, dim3(kPfThreads), 0, stream, static_cast<const uint16_t*>(q), cu_q_lens,
                        static_cast<const uint16_t*>(k_cache), static_cast<const uint16_t*>(v_cache), block_table,
                        seq_lens, out, p.out_dtype == VTC_F32 ? 1 : 0, p.num_q_heads, p.num_kv_heads,
-                       p.max_blocks_per_seq, scale2);
+                       p.max_blocks_per_seq, scale2, shape.xcds, shape.cus / shape.xcds);
   };
   if (scale2 >= 0.f)
     go(prefill_chunk_kernel<T, HW, true>);

@@ -47,17 +47,17 @@ struct CostTerm {                              // (h(new) - h(old)) * multiplier
   }
 };
 
-struct PredictedTerm {                         // Algorithm 3, "adjust the cost of output tokens"
+struct PredictedTerm {                         // per-step adjustment under length prediction (Section 4.4)
   const int32_t* __restrict__ n_output;
   const int32_t* __restrict__ n_predicted;
   const int32_t* __restrict__ finished;
   u64 w_q;
+  // The predicted tokens were paid for at admission.  A token beyond the prediction costs w_q when it is
+  // generated; a request that ends short of its prediction gets the unused part back, w_q per token.
   __device__ __forceinline__ u64 operator()(int r, int) const {
-    const long long delta = (long long)n_output[r] - (long long)n_predicted[r];
-    u64 add = 0ull;
-    if (delta > 0) add += w_q;                                   // prediction used up: pay per token
-    if (finished[r] != 0 && delta < 0) add += w_q * (u64)delta;  // refund the unused pre-payment
-    return add;
+    const long long beyond = (long long)n_output[r] - (long long)n_predicted[r];      // > 0: prediction used up
+    const long long tokens = (beyond > 0 ? 1ll : 0ll) + ((finished[r] != 0 && beyond < 0) ? beyond : 0ll);
+    return w_q * (u64)tokens;
   }
 };
 

@@ -116,7 +116,12 @@ struct DecodeWorkspace {
 
 inline size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
 
-int device_cu_count();   // compute units of the current device (cached per device; 256 when there is no device)
+struct DeviceShape {
+  int cus;    // compute units
+  int xcds;   // accelerator complex dies they are spread over (each with its own L2); 1 if unknown
+};
+DeviceShape device_shape();   // of the current device (cached per device; 256 / 8 when there is no device)
+int device_cu_count();        // device_shape().cus
 
 // The most waves a decode launch uses on the current device.
 inline int decode_wave_bound() {
