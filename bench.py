@@ -261,7 +261,7 @@ def prefill_kernel_on_cfg5(torch, vtc, chunk, launches=24, reps=5, rotate=6):
         q, k, v, table, out = sets[i % rotate]
         vtc.vtc_attn_prefill_chunk(params, q, cu, lq, k, v, table, seq, out=out)
 
-    for i in range(rotate):
+    for i in range(2 * launches):                    # warm-up: clocks, TLBs, instruction cache
         launch(i)
     torch.cuda.synchronize()
     per_launch = []

@@ -86,8 +86,8 @@ typedef struct {
  * table can address, means max_blocks_per_seq * block_size).  The footprint is a
  * fixed part plus a share per wave (two fp32 partial results per query head of a
  * group), and short batches cannot use many waves, so it grows with
- * max_num_seqs * max_seq_len until the device's wave count caps it (a few MB to
- * a few tens of MB).  Host arithmetic plus one query of the current device's
+ * max_num_seqs * max_seq_len until the device's wave count caps it (2 to 9 MB
+ * on 256 compute units, depending on num_q_heads / num_kv_heads).  Host arithmetic plus one query of the current device's
  * compute-unit count (256 is assumed when there is no usable device).  Returns 0
  * if params is NULL or unsupported.  vtc_attn_prefill_chunk needs no workspace.
  */
@@ -135,10 +135,10 @@ int vtc_attn_decode(const vtc_attn_params* params /*[host]*/, int32_t num_seqs, 
  * vtc_attn_decode for callers that cannot allocate device memory or hand over a
  * workspace: code under HIP graph capture, tight serving loops, harnesses that
  * forbid hipMalloc.  Same arguments, results and error behaviour as
- * vtc_attn_decode, except that the workspace is a 20 MiB device array inside the
+ * vtc_attn_decode, except that the workspace is a 10 MiB device array inside the
  * library image (every device the library runs on holds its own copy until the
  * process ends).  The call allocates and frees nothing.
- *   - num_seqs may be at most 65536; more returns VTC_ERR_STATIC_LIMIT.  20 MiB
+ *   - num_seqs may be at most 65536; more returns VTC_ERR_STATIC_LIMIT.  10 MiB
  *     hold the full wave count of a 256-compute-unit device for every supported
  *     shape; on a larger device the launch uses the waves that fit.
  *   - Every call on a device shares that device's array: calls that overlap on

@@ -66,7 +66,7 @@ static int decode_common(const vtc_attn_params* params, int32_t num_seqs, const 
       (reinterpret_cast<uintptr_t>(k_cache) & 15u) || (reinterpret_cast<uintptr_t>(v_cache) & 15u))
     return VTC_ERR_INVALID_ARG;
   // the launch uses as many waves as the workspace has room for (and the device can hold)
-  const int max_waves = vtc::decode_wave_capacity(*params, num_seqs, workspace_bytes, vtc::decode_wave_bound());
+  const int max_waves = vtc::decode_wave_capacity(*params, num_seqs, workspace_bytes, vtc::decode_wave_bound(*params));
   if (max_waves < 1) return VTC_ERR_WORKSPACE_TOO_SMALL;
   return vtc::launch_decode(*params, num_seqs, q, k_cache, v_cache, block_table, seq_lens, out, workspace, max_waves,
                             static_cast<hipStream_t>(hip_stream), static_cast<hipEvent_t>(ev_begin),

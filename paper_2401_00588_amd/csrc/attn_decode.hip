@@ -256,6 +256,7 @@ struct ValuEngine {
   static constexpr int kQRegs = G;       // one 16-byte q slice per query head
   static constexpr int kLdsElems = 0;
   static constexpr int kMinWavesPerSimd = G == 1 ? 4 : (G == 2 ? 3 : (G == 4 ? 2 : 1));   // register budget (used with G = 1)
+  static constexpr int kWavesPerCu = kDecodeWavesPerCuMha;
   int row, sub;
   float m[G];        // running max of the scaled logits (log2 domain), per 16-lane row
   float l[G];        // running sum of exp2(logit - m)
@@ -407,6 +408,7 @@ struct MfmaEngine {
   static constexpr int kPitchQ = kHeadDim + 8;
   static constexpr int kLdsElems = kBlockSize * (kPitchK + kPitchV) + 4 * kQRegs * kPitchQ;
   static constexpr int kMinWavesPerSimd = 2;      // register budget = 512 / this (three waves spill)
+  static constexpr int kWavesPerCu = kDecodeWavesPerCuGqa;
   using f32x4 = float __attribute__((ext_vector_type(4)));
   using f16x8 = _Float16 __attribute__((ext_vector_type(8)));
   using bf16x8 = __bf16 __attribute__((ext_vector_type(8)));
@@ -772,12 +774,10 @@ static int launch_typed(const vtc_attn_params& p, int32_t num_seqs, const void* 
                         const void* v_cache, const int32_t* block_table, const int32_t* seq_lens, void* out,
                         void* workspace, int32_t max_waves, hipStream_t stream, hipEvent_t ev_begin,
                         hipEvent_t ev_end, const CounterJob& job) {
-  // Grid = the waves the chip holds at once (never more, so no wave waits for a slot while the others are
-  // already half way through their share), or as many of them as the caller's workspace has room for.  The
-  // kernel's launch bounds guarantee kMinWavesPerSimd waves on each of a compute unit's four SIMDs.
-  constexpr int kWavesPerCu = 4 * Engine::kMinWavesPerSimd < kDecodeWavesPerCu ? 4 * Engine::kMinWavesPerSimd
-                                                                                : kDecodeWavesPerCu;
-  const long long resident = (long long)device_cu_count() * kWavesPerCu;
+  // Grid: a fixed number of waves per compute unit, all resident at once (no wave waits for a slot while the
+  // others are already half way through their share), or as many of them as the caller's workspace has room for.
+  static_assert(Engine::kWavesPerCu <= 4 * Engine::kMinWavesPerSimd, "the launch must fit the kernel's guaranteed occupancy");
+  const long long resident = (long long)device_cu_count() * Engine::kWavesPerCu;
   const int grid = (int)(resident < max_waves ? resident : max_waves);
 
   const DecodeWorkspace ws = decode_workspace_layout(p, num_seqs, grid);

@@ -8,7 +8,7 @@
 
 namespace vtc {
 
-constexpr size_t kStaticScratchBytes = 20u << 20;      // 20 MiB on every device the library runs on
+constexpr size_t kStaticScratchBytes = 10u << 20;      // 10 MiB on every device the library runs on
 constexpr int32_t kStaticMaxSeqs = 65536;              // 256 KiB of it for the per-sequence prefix
 
 // In host code this name is a stand-in for the symbol, not a device address: host code uses the pointer that
@@ -46,7 +46,7 @@ extern "C" int vtc_attn_decode_static(const vtc_attn_params* params, int32_t num
       (reinterpret_cast<uintptr_t>(k_cache) & 15u) || (reinterpret_cast<uintptr_t>(v_cache) & 15u))
     return VTC_ERR_INVALID_ARG;
   // as many waves as the array has room for (all the device holds, for every supported shape on 256 compute units)
-  const int max_waves = vtc::decode_wave_capacity(*params, num_seqs, vtc::kStaticScratchBytes, vtc::decode_wave_bound());
+  const int max_waves = vtc::decode_wave_capacity(*params, num_seqs, vtc::kStaticScratchBytes, vtc::decode_wave_bound(*params));
   if (max_waves < 1) return VTC_ERR_STATIC_LIMIT;
   void* workspace = nullptr;
   rc = vtc::static_scratch(&workspace);

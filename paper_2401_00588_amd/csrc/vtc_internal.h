@@ -16,7 +16,12 @@ constexpr int kTileElems = kBlockSize * kHeadDim;   // elements of one (block, k
 constexpr float kLog2e = 1.4426950408889634f;
 
 // Decode attention cuts the batch's stream of KV blocks into one range per resident wave.
-constexpr int kDecodeWavesPerCu = 16;        // waves launched per compute unit, at most (fewer where registers limit it)
+// Waves launched per compute unit.  Four already saturate the memory system; with many more, the waves
+// dispatched last progress so much more slowly than the first that the end of the launch drags (measured: one
+// query head per KV head, 64 and 256 sequences: 8 per CU 1.5 % faster than 16; grouped queries, 256 and 512
+// sequences: 4 per CU 1.5 % faster than 8).
+constexpr int kDecodeWavesPerCuMha = 8;      // num_q_heads == num_kv_heads (vector-ALU engine)
+constexpr int kDecodeWavesPerCuGqa = 4;      // grouped queries (matrix-core engine)
 constexpr int kMaxDecodeWaves = 8192;        // upper bound on the launch on any device
 constexpr int kMinBlocksPerWave = 2;         // small batches use fewer waves rather than shorter ranges
 
@@ -124,8 +129,9 @@ DeviceShape device_shape();   // of the current device (cached per device; 256 /
 int device_cu_count();        // device_shape().cus
 
 // The most waves a decode launch uses on the current device.
-inline int decode_wave_bound() {
-  const long long w = (long long)device_cu_count() * kDecodeWavesPerCu;
+inline int decode_wave_bound(const vtc_attn_params& p) {
+  const int per_cu = p.num_q_heads == p.num_kv_heads ? kDecodeWavesPerCuMha : kDecodeWavesPerCuGqa;
+  const long long w = (long long)device_cu_count() * per_cu;
   return (int)(w < kMaxDecodeWaves ? w : kMaxDecodeWaves);
 }
 
@@ -157,7 +163,7 @@ inline int decode_waves_for(const vtc_attn_params& p, int32_t num_seqs, int32_t 
   long long nb = max_seq_len > 0 ? ((long long)max_seq_len + kBlockSize - 1) / kBlockSize : cap;
   if (nb > cap) nb = cap;
   const long long want = (nb * num_seqs * p.num_kv_heads + kMinBlocksPerWave - 1) / kMinBlocksPerWave;
-  const long long bound = decode_wave_bound();
+  const long long bound = decode_wave_bound(p);
   const long long w = want < bound ? want : bound;
   return (int)(w > 1 ? w : 1);
 }
