@@ -40,6 +40,14 @@
  *   seq_lens      int32 [num_seqs]
  * Token p of sequence r lives in block block_table[r][p / block_size], row
  * p % block_size.  Query head h reads KV head h / (num_q_heads/num_kv_heads).
+ *
+ * Block sizes.  The kernels are built for blocks of 16 tokens: a (block, kv head)
+ * tile is then 4 KiB of contiguous K and of V.  The paper's own system pages its
+ * cache one token at a time (Section 5.1); block sizes 1, 2, 4 and 8 are served by
+ * the same entry points through a general path (one wavefront per query row, 16
+ * tokens gathered through the block table at a time) with the same results and
+ * error behaviour.  That path is not tuned, takes no workspace (the workspace
+ * arguments are ignored) and makes vtc_step_decode launch its charge separately.
  */
 #ifndef VTC_H_
 #define VTC_H_
@@ -56,7 +64,7 @@ typedef enum { VTC_F16 = 0, VTC_BF16 = 1, VTC_F32 = 2 /* output rows only */ } v
 enum {
   VTC_OK = 0,
   VTC_ERR_INVALID_ARG = -1,         /* null pointer, negative size, inconsistent sizes   */
-  VTC_ERR_UNSUPPORTED = -2,         /* head_dim != 128, block_size != 16, unknown dtype,
+  VTC_ERR_UNSUPPORTED = -2,         /* head_dim != 128, block_size not 1/2/4/8/16, unknown dtype,
                                        out_dtype neither dtype nor VTC_F32,
                                        num_q_heads/num_kv_heads not in {1,2,4,8}          */
   VTC_ERR_WORKSPACE_TOO_SMALL = -3, /* workspace_bytes < vtc_attn_workspace_bytes(...)   */
@@ -70,7 +78,8 @@ typedef struct {
   int32_t num_q_heads;        /* Hq                                              */
   int32_t num_kv_heads;       /* Hkv, must divide Hq                             */
   int32_t head_dim;           /* 128                                             */
-  int32_t block_size;         /* tokens per KV block: 16                         */
+  int32_t block_size;         /* tokens per KV block: 16 (the tuned kernels), or 1,
+                                 2, 4, 8 (a general path, see below)             */
   int32_t max_blocks_per_seq; /* row stride of block_table                       */
   int32_t dtype;              /* vtc_dtype of q, k_cache and v_cache: F16 or BF16 */
   float scale;                /* logit scale, normally 1/sqrt(head_dim)          */
@@ -344,7 +353,8 @@ int vtc_kv_append(const vtc_attn_params* params /*[host]*/, int32_t num_seqs, co
  * exclusive prefix sums of seq_lens; max_seq_len is a host-side upper bound on
  * seq_lens (sizes the launch).  The attention kernels address whole blocks
  * (block_table[r][b] times the block stride), which is this formula at
- * p = b * block_size; vtc_kv_append addresses single rows with it.
+ * p = b * block_size; vtc_kv_append and the general path for small blocks address
+ * single rows with it.
  */
 int vtc_debug_gather_slots(const vtc_attn_params* params /*[host]*/, int32_t num_seqs,
                            const int32_t* block_table, const int32_t* seq_lens,

@@ -36,7 +36,7 @@ const char* vtc_strerror(int code) {
     case VTC_OK: return "success";
     case VTC_ERR_INVALID_ARG: return "invalid argument (null pointer, negative or inconsistent size)";
     case VTC_ERR_UNSUPPORTED:
-      return "unsupported configuration (need head_dim 128, block_size 16, fp16/bf16, "
+      return "unsupported configuration (need head_dim 128, block_size 1, 2, 4, 8 or 16, fp16/bf16, "
              "num_q_heads/num_kv_heads in {1,2,4,8})";
     case VTC_ERR_WORKSPACE_TOO_SMALL: return "workspace smaller than vtc_attn_workspace_bytes()";
     case VTC_ERR_HIP: return "HIP runtime error (launch failed or no usable device)";
@@ -60,16 +60,26 @@ static int decode_common(const vtc_attn_params* params, int32_t num_seqs, const 
   if (rc != VTC_OK) return rc;
   if (num_seqs < 0) return VTC_ERR_INVALID_ARG;
   if (num_seqs == 0) return VTC_OK;
-  if (!q || !k_cache || !v_cache || !block_table || !seq_lens || !out || !workspace) return VTC_ERR_INVALID_ARG;
-  if ((reinterpret_cast<uintptr_t>(workspace) & 255u) != 0) return VTC_ERR_INVALID_ARG;
+  if (!q || !k_cache || !v_cache || !block_table || !seq_lens || !out) return VTC_ERR_INVALID_ARG;
   if ((reinterpret_cast<uintptr_t>(q) & 15u) || (reinterpret_cast<uintptr_t>(out) & 15u) ||
       (reinterpret_cast<uintptr_t>(k_cache) & 15u) || (reinterpret_cast<uintptr_t>(v_cache) & 15u))
     return VTC_ERR_INVALID_ARG;
+  hipStream_t stream = static_cast<hipStream_t>(hip_stream);
+  if (params->block_size != vtc::kBlockSize) {            // small blocks: the general path, which needs no workspace
+    if (ev_begin) (void)hipEventRecord(static_cast<hipEvent_t>(ev_begin), stream);
+    rc = vtc::launch_attend_general(*params, num_seqs, q, nullptr, 1, k_cache, v_cache, block_table, seq_lens, out, stream);
+    if (ev_end) (void)hipEventRecord(static_cast<hipEvent_t>(ev_end), stream);
+    if (rc == VTC_OK && job.n > 0)
+      rc = vtc::launch_counter_update(reinterpret_cast<int64_t*>(job.counters), job.num_clients, job.client_ids, job.n_in,
+                                      job.n_out, job.n, (int64_t)job.w_p, (int64_t)job.w_q, stream);
+    return rc;
+  }
+  if (!workspace || (reinterpret_cast<uintptr_t>(workspace) & 255u) != 0) return VTC_ERR_INVALID_ARG;
   // the launch uses as many waves as the workspace has room for (and the device can hold)
   const int max_waves = vtc::decode_wave_capacity(*params, num_seqs, workspace_bytes, vtc::decode_wave_bound(*params));
   if (max_waves < 1) return VTC_ERR_WORKSPACE_TOO_SMALL;
   return vtc::launch_decode(*params, num_seqs, q, k_cache, v_cache, block_table, seq_lens, out, workspace, max_waves,
-                            static_cast<hipStream_t>(hip_stream), static_cast<hipEvent_t>(ev_begin),
+                            stream, static_cast<hipEvent_t>(ev_begin),
                             static_cast<hipEvent_t>(ev_end), job);
 }
 
@@ -136,6 +146,9 @@ int vtc_attn_prefill_chunk(const vtc_attn_params* params, int32_t num_seqs, cons
   if ((reinterpret_cast<uintptr_t>(q) & 15u) || (reinterpret_cast<uintptr_t>(out) & 15u) ||
       (reinterpret_cast<uintptr_t>(k_cache) & 15u) || (reinterpret_cast<uintptr_t>(v_cache) & 15u))
     return VTC_ERR_INVALID_ARG;
+  if (params->block_size != vtc::kBlockSize)
+    return vtc::launch_attend_general(*params, num_seqs, q, cu_q_lens, max_q_len, k_cache, v_cache, block_table, seq_lens,
+                                      out, static_cast<hipStream_t>(hip_stream));
   return vtc::launch_prefill(*params, num_seqs, q, cu_q_lens, max_q_len, k_cache, v_cache, block_table,
                              seq_lens, out, static_cast<hipStream_t>(hip_stream));
 }

@@ -45,6 +45,9 @@ extern "C" int vtc_attn_decode_static(const vtc_attn_params* params, int32_t num
   if ((reinterpret_cast<uintptr_t>(q) & 15u) || (reinterpret_cast<uintptr_t>(out) & 15u) ||
       (reinterpret_cast<uintptr_t>(k_cache) & 15u) || (reinterpret_cast<uintptr_t>(v_cache) & 15u))
     return VTC_ERR_INVALID_ARG;
+  if (params->block_size != vtc::kBlockSize)              // small blocks: the general path uses no scratch at all
+    return vtc::launch_attend_general(*params, num_seqs, q, nullptr, 1, k_cache, v_cache, block_table, seq_lens, out,
+                                      static_cast<hipStream_t>(hip_stream));
   // as many waves as the array has room for (all the device holds, for every supported shape on 256 compute units)
   const int max_waves = vtc::decode_wave_capacity(*params, num_seqs, vtc::kStaticScratchBytes, vtc::decode_wave_bound(*params));
   if (max_waves < 1) return VTC_ERR_STATIC_LIMIT;

@@ -12,13 +12,13 @@ constexpr int kAppendTokens = 8;       // new tokens of one sequence per workgro
 __global__ __launch_bounds__(kAppendThreads) void kv_append_kernel(
     const uint16_t* __restrict__ k_new, const uint16_t* __restrict__ v_new, const int32_t* __restrict__ cu_new_lens,
     uint16_t* __restrict__ k_cache, uint16_t* __restrict__ v_cache, const int32_t* __restrict__ block_table,
-    const int32_t* __restrict__ seq_lens, int32_t num_kv_heads, int32_t max_blocks_per_seq) {
+    const int32_t* __restrict__ seq_lens, int32_t num_kv_heads, int32_t max_blocks_per_seq, int32_t block_size) {
   const int r = blockIdx.x;
   const int first = cu_new_lens[r];
   const int n_new = cu_new_lens[r + 1] - first;
   const int i0 = blockIdx.y * kAppendTokens;
   if (i0 >= n_new) return;
-  const int s_len = min(max(seq_lens[r], 0), max_blocks_per_seq * kBlockSize);
+  const int s_len = min(max(seq_lens[r], 0), max_blocks_per_seq * block_size);
   const int pieces_per_token = num_kv_heads * (kHeadDim / 8);          // 16-byte pieces of one token's K (or V)
   const int n_tok = min(kAppendTokens, n_new - i0);
   for (int it = threadIdx.x; it < n_tok * pieces_per_token; it += kAppendThreads) {
@@ -29,8 +29,8 @@ __global__ __launch_bounds__(kAppendThreads) void kv_append_kernel(
     const int p = s_len - n_new + i;                                   // absolute position
     if (p < 0) continue;                                               // seq_lens shorter than the append: nothing to place
     const size_t src = ((size_t)(first + i) * num_kv_heads + head) * kHeadDim + c16 * 8;
-    const int32_t slot = slot_of(block_table + (size_t)r * max_blocks_per_seq, p);   // physical block * 16 + row
-    const size_t dst = (((size_t)(slot / kBlockSize) * num_kv_heads + head) * kBlockSize + slot % kBlockSize) * kHeadDim + c16 * 8;
+    const int32_t slot = slot_of(block_table + (size_t)r * max_blocks_per_seq, p, block_size);   // physical block * block_size + row
+    const size_t dst = cache_row_offset(slot, head, num_kv_heads, block_size) + c16 * 8;
     *reinterpret_cast<u32x4*>(k_cache + dst) = *reinterpret_cast<const u32x4*>(k_new + src);
     *reinterpret_cast<u32x4*>(v_cache + dst) = *reinterpret_cast<const u32x4*>(v_new + src);
   }
@@ -44,7 +44,7 @@ int launch_kv_append(const vtc_attn_params& p, int32_t num_seqs, const void* k_n
   hipLaunchKernelGGL(kv_append_kernel, dim3(num_seqs, gy), dim3(kAppendThreads), 0, stream,
                      static_cast<const uint16_t*>(k_new), static_cast<const uint16_t*>(v_new), cu_new_lens,
                      static_cast<uint16_t*>(k_cache), static_cast<uint16_t*>(v_cache), block_table, seq_lens,
-                     p.num_kv_heads, p.max_blocks_per_seq);
+                     p.num_kv_heads, p.max_blocks_per_seq, p.block_size);
   return hipGetLastError() == hipSuccess ? VTC_OK : VTC_ERR_HIP;
 }
 

@@ -10,7 +10,7 @@
 namespace vtc {
 
 constexpr int kHeadDim = 128;       // the only supported head_dim
-constexpr int kBlockSize = 16;      // tokens per KV block
+constexpr int kBlockSize = 16;      // tokens per KV block of the tuned kernels (smaller powers of two: general path)
 constexpr int kWave = 64;           // CDNA wavefront
 constexpr int kTileElems = kBlockSize * kHeadDim;   // elements of one (block, kv head) K or V tile
 constexpr float kLog2e = 1.4426950408889634f;
@@ -43,10 +43,14 @@ using bf16x2 = __bf16 __attribute__((ext_vector_type(2)));
 struct F16 {};
 struct BF16 {};
 
-// Physical slot of token p of a sequence whose block-table row is `row`.
-// Paged KV cache (Section 5.1 of the paper names it; this is the usual index).
-__device__ __forceinline__ int32_t slot_of(const int32_t* __restrict__ row, int32_t p) {
-  return row[p / kBlockSize] * kBlockSize + p % kBlockSize;
+// Physical slot of token p of a sequence whose block-table row is `row`, for blocks of `bs` tokens.
+// Paged KV cache (Section 5.1 of the paper names it, with blocks of one token; this is the usual index).
+__device__ __forceinline__ int32_t slot_of(const int32_t* __restrict__ row, int32_t p, int32_t bs) {
+  return row[p / bs] * bs + p % bs;
+}
+// Element offset of the 128-wide row of (slot, kv head) in a cache laid out [block, kv head, row of the block, dim].
+__device__ __forceinline__ size_t cache_row_offset(int32_t slot, int32_t head, int32_t num_kv_heads, int32_t bs) {
+  return (((size_t)(slot / bs) * num_kv_heads + head) * bs + slot % bs) * kHeadDim;
 }
 
 // ---- 16-bit element helpers -------------------------------------------------
@@ -160,7 +164,7 @@ inline DecodeWorkspace decode_workspace_layout(const vtc_attn_params& p, int32_t
 // table's capacity): every wave gets at least kMinBlocksPerWave KV blocks.
 inline int decode_waves_for(const vtc_attn_params& p, int32_t num_seqs, int32_t max_seq_len) {
   const long long cap = (long long)p.max_blocks_per_seq;
-  long long nb = max_seq_len > 0 ? ((long long)max_seq_len + kBlockSize - 1) / kBlockSize : cap;
+  long long nb = max_seq_len > 0 ? ((long long)max_seq_len + p.block_size - 1) / p.block_size : cap;
   if (nb > cap) nb = cap;
   const long long want = (nb * num_seqs * p.num_kv_heads + kMinBlocksPerWave - 1) / kMinBlocksPerWave;
   const long long bound = decode_wave_bound(p);
@@ -186,7 +190,9 @@ inline int check_params(const vtc_attn_params* p) {
   if (p->num_q_heads % p->num_kv_heads != 0) return VTC_ERR_UNSUPPORTED;
   const int g = p->num_q_heads / p->num_kv_heads;
   if (g != 1 && g != 2 && g != 4 && g != 8) return VTC_ERR_UNSUPPORTED;
-  if (p->head_dim != kHeadDim || p->block_size != kBlockSize) return VTC_ERR_UNSUPPORTED;
+  if (p->head_dim != kHeadDim) return VTC_ERR_UNSUPPORTED;
+  if (p->block_size != 1 && p->block_size != 2 && p->block_size != 4 && p->block_size != 8 && p->block_size != kBlockSize)
+    return VTC_ERR_UNSUPPORTED;
   if (p->dtype != VTC_F16 && p->dtype != VTC_BF16) return VTC_ERR_UNSUPPORTED;
   if (p->out_dtype != p->dtype && p->out_dtype != VTC_F32) return VTC_ERR_UNSUPPORTED;
   return VTC_OK;
@@ -209,6 +215,11 @@ int launch_decode(const vtc_attn_params& p, int32_t num_seqs, const void* q, con
                   const void* v_cache, const int32_t* block_table, const int32_t* seq_lens, void* out,
                   void* workspace, int32_t max_waves, hipStream_t stream, hipEvent_t ev_begin, hipEvent_t ev_end,
                   const CounterJob& counter_job);
+// Attention for KV blocks of fewer than 16 tokens (one wave per query row, no workspace): decode when cu_q_lens
+// is null (one query row per sequence), else the causal prefill chunk.
+int launch_attend_general(const vtc_attn_params& p, int32_t num_seqs, const void* q, const int32_t* cu_q_lens,
+                          int32_t max_q_len, const void* k_cache, const void* v_cache, const int32_t* block_table,
+                          const int32_t* seq_lens, void* out, hipStream_t stream);
 int launch_prefill(const vtc_attn_params& p, int32_t num_seqs, const void* q, const int32_t* cu_q_lens,
                    int32_t max_q_len, const void* k_cache, const void* v_cache, const int32_t* block_table,
                    const int32_t* seq_lens, void* out, hipStream_t stream);

@@ -75,7 +75,7 @@ def test_workspace_bytes_is_host_arithmetic(lib):
 
 
 @pytest.mark.parametrize("kw,code", [
-    (dict(head_dim=64), -2), (dict(block_size=32), -2), (dict(dtype=7), -2),
+    (dict(head_dim=64), -2), (dict(block_size=32), -2), (dict(block_size=3), -2), (dict(block_size=0), -2), (dict(dtype=7), -2),
     (dict(num_q_heads=32, num_kv_heads=5), -2), (dict(num_q_heads=48, num_kv_heads=16), -2),
     (dict(num_q_heads=0), -1), (dict(num_kv_heads=-1), -1), (dict(max_blocks_per_seq=0), -1),
     (dict(scale=float("nan")), -1),
