@@ -37,7 +37,7 @@ EVENT_EVERY = 5                # steps between two kernel-level HIP event pairs
 # by the copy-kernel calibration (profiles/decode_attend_cfg3_hbm_bytes.md).  Valid only for the kernel
 # source the counters were taken with: keyed by the SHA-256 of the two files that define that kernel.
 DECODE_TRAFFIC_CFG3 = {
-    "a020f10e3bf806cb": 4062405553,
+    "7ec1c102d2a80765": 4060119022,
 }
 
 
