@@ -4,11 +4,13 @@
 // element of every running request is read exactly once per step.
 //
 // Decomposition.  Order all (sequence r, kv head h, KV block b) triples of the batch
-// as r-major, then h, then b, and call that sequence of gtot blocks the *stream*.
-// The stream is cut into W equal ranges, one per resident wavefront, regardless of
-// where sequences begin and end, so every wave moves the same number of bytes:
-//   plan    blocks per sequence -> exclusive prefix; then for each wave the (r, h, b)
-//           at which its range starts and the range length.  Batches of up to 1024
+// as r-major, then h, then b, and call that sequence of blocks the *stream*.
+// The stream is cut into W ranges of equal *cost*, one per resident wavefront, regardless
+// of where sequences begin and end.  A block costs one unit and so does every (r, h)
+// that begins (closing it -- merging the softmax rows, normalising, writing -- takes a
+// wave about as long as one block), so every wave needs about the same time:
+//   plan    units per sequence -> exclusive prefix; then for each wave the (r, h, b)
+//           at which its range starts and its number of blocks.  Batches of up to 1024
 //           sequences need no launch for this: every attend wave derives its own
 //           range from seq_lens in registers.  Larger batches run a one-workgroup
 //           planning kernel first.
@@ -38,8 +40,12 @@ namespace vtc {
 
 constexpr int kPlanThreads = 1024;
 
-// Start of wave w's range in the stream, floor(gtot * w / waves), from quot = gtot / waves and
-// rem = gtot % waves (rem * w < 2^26 because waves <= kMaxDecodeWaves): no 64-bit division.
+// The stream in cost units: sequence r with nb_r > 0 blocks takes Hkv * (nb_r + kPieceUnits) units, head by head,
+// each head's kPieceUnits of overhead first and its blocks after them.  A cut that falls into the overhead
+// starts the range at block 0 of that head.
+//
+// Start of wave w's range, floor(total * w / waves), from quot = total / waves and rem = total % waves
+// (rem * w < 2^26 because waves <= kMaxDecodeWaves): no 64-bit division per lookup.
 struct RangeMap {
   long long quot;
   uint32_t rem;
@@ -48,19 +54,41 @@ struct RangeMap {
     return quot * (long long)w + (long long)(rem * (uint32_t)w / waves);
   }
 };
+__device__ __forceinline__ RangeMap make_range_map(long long total, int waves) {
+  if (waves <= 0) return RangeMap{0, 0u, 1u};
+  if (total <= 0xffffffffll)                         // the usual case: 32-bit division
+    return RangeMap{(long long)((uint32_t)total / (uint32_t)waves), (uint32_t)total % (uint32_t)waves, (uint32_t)waves};
+  return RangeMap{total / waves, (uint32_t)(total % waves), (uint32_t)waves};
+}
+
+// Where a position v of the unit stream lies, given the sequence r that contains it: p_blocks / p_seqs = blocks /
+// non-empty sequences before r, nb = blocks of r.  Returns (r, kv head, block, real blocks of the stream before v).
+struct UnitPos {
+  int r, h, b;
+  long long blocks_before;
+};
+__device__ __forceinline__ UnitPos unit_pos(long long v, int r, long long p_blocks, long long p_seqs, uint32_t nb,
+                                            int num_kv_heads) {
+  const uint32_t per_head = nb + kPieceUnits;
+  const uint32_t off = (uint32_t)(v - (p_blocks + p_seqs * kPieceUnits) * num_kv_heads);     // < per_head * Hkv < 2^31
+  const uint32_t h = off / per_head, u = off - h * per_head;
+  const uint32_t b = u > (uint32_t)kPieceUnits ? u - kPieceUnits : 0u;
+  return UnitPos{r, (int)h, (int)b, p_blocks * num_kv_heads + (long long)h * nb + b};
+}
 
 // ------------------------------------------------------------------ plan ----
-constexpr int kPlanLdsSeqs = 8192;     // sequences whose block prefix is also kept in LDS for the range search
+constexpr int kPlanLdsSeqs = 4096;     // sequences whose prefix is also kept in LDS for the range search
 
 __global__ __launch_bounds__(kPlanThreads) void decode_plan_kernel(const int32_t* __restrict__ seq_lens,
                                                                    int32_t num_seqs, int32_t num_kv_heads,
                                                                    int32_t max_tokens, int32_t max_waves,
                                                                    DecodeHeader* __restrict__ header,
-                                                                   int32_t* __restrict__ seg_prefix,
+                                                                   unsigned long long* __restrict__ seg_prefix,
                                                                    int4* __restrict__ wave_desc) {
-  __shared__ int32_t prefix_lds[kPlanLdsSeqs + 1];
-  __shared__ int32_t wave_sums[kPlanThreads / kWave];
-  __shared__ int32_t carry;
+  // a prefix entry: non-empty sequences before r in the high half, their blocks in the low half
+  __shared__ unsigned long long prefix_lds[kPlanLdsSeqs + 1];
+  __shared__ unsigned long long wave_sums[kPlanThreads / kWave];
+  __shared__ unsigned long long carry;
   const int tid = threadIdx.x;
   const int lane = tid & (kWave - 1);
   const int wid = tid / kWave;
@@ -68,21 +96,24 @@ __global__ __launch_bounds__(kPlanThreads) void decode_plan_kernel(const int32_t
   __syncthreads();
   for (int base = 0; base < num_seqs; base += kPlanThreads) {
     const int r = base + tid;
-    int32_t n = 0;
-    if (r < num_seqs) n = (min(max(seq_lens[r], 0), max_tokens) + kBlockSize - 1) / kBlockSize;
+    unsigned long long n = 0;
+    if (r < num_seqs) {
+      const uint32_t nb = (uint32_t)(min(max(seq_lens[r], 0), max_tokens) + kBlockSize - 1) / kBlockSize;
+      n = nb > 0 ? (1ull << 32) | nb : 0ull;
+    }
     // inclusive scan inside the wave, then across the 16 waves
-    int32_t x = n;
+    unsigned long long x = n;
 #pragma unroll
     for (int off = 1; off < kWave; off <<= 1) {
-      const int32_t y = __shfl_up(x, off);
+      const unsigned long long y = __shfl_up(x, off);
       if (lane >= off) x += y;
     }
     if (lane == kWave - 1) wave_sums[wid] = x;
     __syncthreads();
-    int32_t before = carry;
+    unsigned long long before = carry;
     for (int j = 0; j < wid; ++j) before += wave_sums[j];
     if (r < num_seqs) {
-      const int32_t excl = before + x - n;
+      const unsigned long long excl = before + x - n;
       seg_prefix[r] = excl;
       if (r < kPlanLdsSeqs) prefix_lds[r] = excl;
     }
@@ -90,42 +121,47 @@ __global__ __launch_bounds__(kPlanThreads) void decode_plan_kernel(const int32_t
     if (tid == kPlanThreads - 1) carry = before + x;
     __syncthreads();
   }
-  const int32_t total_blocks = carry;
+  const unsigned long long total = carry;
   if (tid == 0) {
-    seg_prefix[num_seqs] = total_blocks;
-    if (num_seqs <= kPlanLdsSeqs) prefix_lds[num_seqs] = total_blocks;
+    seg_prefix[num_seqs] = total;
+    if (num_seqs <= kPlanLdsSeqs) prefix_lds[num_seqs] = total;
   }
-  const long long gtot = (long long)total_blocks * num_kv_heads;
-  // every active wave gets at least kMinBlocksPerWave blocks
-  const long long want = (gtot + kMinBlocksPerWave - 1) / kMinBlocksPerWave;
+  const long long total_blocks = (long long)(total & 0xffffffffull), total_seqs = (long long)(total >> 32);
+  const long long utot = (total_blocks + total_seqs * kPieceUnits) * num_kv_heads;
+  // every active wave gets at least kMinUnitsPerWave units, i.e. at least one block
+  const long long want = utot / kMinUnitsPerWave;
   const int waves = (int)(want < (long long)max_waves ? want : (long long)max_waves);
-  RangeMap map{0, 0u, 1u};
-  if (waves > 0) map = RangeMap{gtot / waves, (uint32_t)(gtot % waves), (uint32_t)waves};
+  const RangeMap map = make_range_map(utot, waves);
   if (tid == 0) {
-    header->gtot = gtot;
+    header->gtot = utot;
     header->quot = map.quot;
     header->rem = (int)map.rem;
     header->waves = waves;
   }
   __syncthreads();                                           // the prefix is complete and visible to the workgroup
   const bool in_lds = num_seqs <= kPlanLdsSeqs;
+  auto units_before = [&](int r) {                           // units of the sequences before r, per kv head
+    const unsigned long long e = in_lds ? prefix_lds[r] : seg_prefix[r];
+    return (long long)(e & 0xffffffffull) + (long long)(e >> 32) * kPieceUnits;
+  };
+  auto locate = [&](long long v) {                           // v < utot
+    // the sequence r with units_before(r) * Hkv <= v < units_before(r + 1) * Hkv
+    int lo = 0, hi = num_seqs - 1;
+    while (lo < hi) {
+      const int mid = (lo + hi) >> 1;
+      if (units_before(mid + 1) * num_kv_heads > v) hi = mid; else lo = mid + 1;
+    }
+    const unsigned long long e0 = in_lds ? prefix_lds[lo] : seg_prefix[lo];
+    const unsigned long long e1 = in_lds ? prefix_lds[lo + 1] : seg_prefix[lo + 1];
+    return unit_pos(v, lo, (long long)(e0 & 0xffffffffull), (long long)(e0 >> 32),
+                    (uint32_t)((e1 & 0xffffffffull) - (e0 & 0xffffffffull)), num_kv_heads);
+  };
   for (int w = tid; w < max_waves; w += kPlanThreads) {
     int4 d = make_int4(0, 0, 0, 0);
     if (w < waves) {
-      const long long g = map.start(w);
-      const long long n = map.start(w + 1) - g;
-      // the sequence r with prefix[r] * Hkv <= g < prefix[r+1] * Hkv
-      int lo = 0, hi = num_seqs - 1;
-      while (lo < hi) {
-        const int mid = (lo + hi) >> 1;
-        const int32_t pm = in_lds ? prefix_lds[mid + 1] : seg_prefix[mid + 1];
-        if ((long long)pm * num_kv_heads > g) hi = mid; else lo = mid + 1;
-      }
-      const int32_t p0 = in_lds ? prefix_lds[lo] : seg_prefix[lo];
-      const int32_t p1 = in_lds ? prefix_lds[lo + 1] : seg_prefix[lo + 1];
-      const int nb = p1 - p0;
-      const uint32_t off = (uint32_t)(g - (long long)p0 * num_kv_heads);   // < nb * Hkv < 2^31
-      d = make_int4(lo, (int)(off / (uint32_t)nb), (int)(off % (uint32_t)nb), (int)n);
+      const UnitPos p0 = locate(map.start(w));
+      const long long end_blocks = w + 1 < waves ? locate(map.start(w + 1)).blocks_before : total_blocks * num_kv_heads;
+      d = make_int4(p0.r, p0.h, p0.b, (int)(end_blocks - p0.blocks_before));
     }
     wave_desc[w] = d;
   }
@@ -133,8 +169,8 @@ __global__ __launch_bounds__(kPlanThreads) void decode_plan_kernel(const int32_t
 
 // ------------------------------------------------------------- self-plan ----
 // The same plan without a launch, for batches of at most 64 x 16 sequences: every wave computes
-// the block prefix in registers (lane i holds sequences i*c .. i*c+c-1, c = ceil(N / 64)) and looks
-// up only its own range start.  Returns (r, h, b, n_blocks); n_blocks = 0 for a wave without a range.
+// the prefix in registers (lane i holds sequences i*c .. i*c+c-1, c = ceil(N / 64)) and looks
+// up only the two ends of its own range.  Returns (r, h, b, n_blocks); n_blocks = 0 for a wave without a range.
 // Wave 0 also writes the header that the merge kernel reads.
 constexpr int kSelfPlanPerLane = 16;
 constexpr int kSelfPlanMaxSeqs = kWave * kSelfPlanPerLane;
@@ -172,63 +208,71 @@ __device__ __forceinline__ int4 self_plan(const int32_t* __restrict__ seq_lens, 
       for (int j = 0; j < 4; ++j) nbv[c + j] = c + j < per_lane ? lens_lds[first + c + j] : 0;
     }
   }
-  int mine = 0;
+  int mine_b = 0, mine_s = 0;              // blocks and non-empty sequences of this lane's run
 #pragma unroll
-  for (int j = 0; j < kSelfPlanPerLane; ++j) mine += nbv[j];
-  int incl = mine;
+  for (int j = 0; j < kSelfPlanPerLane; ++j) {
+    mine_b += nbv[j];
+    mine_s += nbv[j] > 0 ? 1 : 0;
+  }
+  int incl_b = mine_b, incl_s = mine_s;
 #pragma unroll
   for (int off = 1; off < kWave; off <<= 1) {
-    const int y = __shfl_up(incl, off);
-    if (lane >= off) incl += y;
+    const int yb = __shfl_up(incl_b, off), ys = __shfl_up(incl_s, off);
+    if (lane >= off) {
+      incl_b += yb;
+      incl_s += ys;
+    }
   }
-  const int total_blocks = __builtin_amdgcn_readlane(incl, kWave - 1);
-  const int excl = incl - mine;                                // blocks of all sequences before this lane's
-  const long long gtot = (long long)total_blocks * num_kv_heads;
-  const long long want = (gtot + kMinBlocksPerWave - 1) / kMinBlocksPerWave;
+  const int total_blocks = __builtin_amdgcn_readlane(incl_b, kWave - 1);
+  const int total_seqs = __builtin_amdgcn_readlane(incl_s, kWave - 1);
+  const int excl_b = incl_b - mine_b, excl_s = incl_s - mine_s;      // of all sequences before this lane's
+  const int excl_u = excl_b + excl_s * kPieceUnits;                   // units before this lane's run, per kv head
+  const long long utot = ((long long)total_blocks + (long long)total_seqs * kPieceUnits) * num_kv_heads;
+  const bool narrow = utot <= 0xffffffffll;                           // the usual case: 32-bit divisions
+  const long long want = utot / kMinUnitsPerWave;                     // every active wave gets at least one block
   const int waves = (int)(want < (long long)max_waves ? want : (long long)max_waves);
-  RangeMap map{0, 0u, 1u};
-  if (waves > 0) {
-    if (gtot <= 0xffffffffll)                                  // the usual case: 32-bit division
-      map = RangeMap{(long long)((uint32_t)gtot / (uint32_t)waves), (uint32_t)gtot % (uint32_t)waves, (uint32_t)waves};
-    else
-      map = RangeMap{gtot / waves, (uint32_t)(gtot % waves), (uint32_t)waves};
-  }
+  const RangeMap map = make_range_map(utot, waves);
   if (wave == 0 && lane == 0) {
-    header->gtot = gtot;
+    header->gtot = utot;
     header->quot = map.quot;
     header->rem = (int)map.rem;
     header->waves = waves;
   }
   if (wave >= waves) return make_int4(0, 0, 0, 0);
-  const long long g = map.start(wave);
-  const long long n = map.start(wave + 1) - g;
-  // Sequence r owns the stream positions [Hkv * before_r, Hkv * (before_r + nb_r)), so g lies in the
-  // sequence whose block range [before_r, before_r + nb_r) contains floor(g / Hkv).
-  const int gq = gtot <= 0xffffffffll ? (int)((uint32_t)g / (uint32_t)num_kv_heads) : (int)(g / num_kv_heads);
-  // the prefix is non-decreasing over the lanes: the last lane that starts at or before g owns it
-  const unsigned long long below = __ballot(excl <= gq);
-  const int owner = __builtin_amdgcn_readfirstlane(__popcll(below) - 1);
-  int before = excl, found_r = 0, found_before = 0, found_nb = 1;
+  auto locate = [&](long long v) {                                    // v < utot
+    // Sequence r owns the positions [Hkv * before_r, Hkv * (before_r + units_r)), so v lies in the
+    // sequence whose unit range [before_r, before_r + units_r) contains floor(v / Hkv).
+    const int vq = narrow ? (int)((uint32_t)v / (uint32_t)num_kv_heads) : (int)(v / num_kv_heads);
+    // the prefix is non-decreasing over the lanes: the last lane that starts at or before vq owns it
+    const unsigned long long below = __ballot(excl_u <= vq);
+    const int owner = __builtin_amdgcn_readfirstlane(__popcll(below) - 1);
+    int before_b = excl_b, before_s = excl_s, found_r = 0, found_b = 0, found_s = 0, found_nb = 1;
 #pragma unroll
-  for (int c = 0; c < kSelfPlanPerLane; c += 4) {
-    if (c < per_lane) {
+    for (int c = 0; c < kSelfPlanPerLane; c += 4) {
+      if (c < per_lane) {
 #pragma unroll
-      for (int j = 0; j < 4; ++j) {
-        const int nb = nbv[c + j];
-        if (nb > 0 && before <= gq && gq < before + nb) {
-          found_r = first + c + j;
-          found_before = before;
-          found_nb = nb;
+        for (int j = 0; j < 4; ++j) {
+          const int nb = nbv[c + j];
+          const int before_u = before_b + before_s * kPieceUnits;
+          if (nb > 0 && before_u <= vq && vq < before_u + nb + kPieceUnits) {
+            found_r = first + c + j;
+            found_b = before_b;
+            found_s = before_s;
+            found_nb = nb;
+          }
+          before_b += nb;
+          before_s += nb > 0 ? 1 : 0;
         }
-        before += nb;
       }
     }
-  }
-  const int r = __builtin_amdgcn_readlane(found_r, owner);
-  const int p0 = __builtin_amdgcn_readlane(found_before, owner);
-  const uint32_t nb = (uint32_t)__builtin_amdgcn_readlane(found_nb, owner);
-  const uint32_t off = (uint32_t)(g - (long long)p0 * num_kv_heads);       // < nb * Hkv < 2^31
-  return make_int4(r, (int)(off / nb), (int)(off % nb), (int)n);
+    return unit_pos(v, __builtin_amdgcn_readlane(found_r, owner), __builtin_amdgcn_readlane(found_b, owner),
+                    __builtin_amdgcn_readlane(found_s, owner), (uint32_t)__builtin_amdgcn_readlane(found_nb, owner),
+                    num_kv_heads);
+  };
+  const UnitPos p0 = locate(map.start(wave));
+  const long long end_blocks =
+      wave + 1 < waves ? locate(map.start(wave + 1)).blocks_before : (long long)total_blocks * num_kv_heads;
+  return make_int4(p0.r, p0.h, p0.b, (int)(end_blocks - p0.blocks_before));
 }
 
 // ---------------------------------------------------------------- attend ----
@@ -740,7 +784,7 @@ __global__ __launch_bounds__(kWave * G) void decode_merge_kernel(const DecodeHea
   if (d.z > wave_desc[w - 1].w) return;                  // the beginning lies before wave w-1: an earlier block merges it
   const int nb = (min(max(seq_lens[d.x], 0), max_tokens) + kBlockSize - 1) / kBlockSize;
   const RangeMap map{header->quot, (uint32_t)header->rem, (uint32_t)waves};
-  const long long g1 = map.start(w) + (nb - d.z);         // end of the sequence-head in the stream
+  const long long g1 = map.start(w) + (nb - d.z);         // end of the sequence-head in the unit stream (only blocks lie between)
   {
     // wave w-1 holds the beginning (its slot 1); waves w.. hold continuations (their slot 0)
     float m = part_ml[((size_t)(w - 1) * 2 + 1) * group + g].x;
@@ -845,7 +889,7 @@ static int launch_typed(const vtc_attn_params& p, int32_t num_seqs, const void* 
   const DecodeWorkspace ws = decode_workspace_layout(p, num_seqs, grid);
   char* base = static_cast<char*>(workspace);
   DecodeHeader* header = reinterpret_cast<DecodeHeader*>(base + ws.header_off);
-  int32_t* seg_prefix = reinterpret_cast<int32_t*>(base + ws.seg_prefix_off);
+  unsigned long long* seg_prefix = reinterpret_cast<unsigned long long*>(base + ws.seg_prefix_off);
   int4* wave_desc = reinterpret_cast<int4*>(base + ws.wave_desc_off);
   float2* part_ml = reinterpret_cast<float2*>(base + ws.ml_off);
   float* part_acc = reinterpret_cast<float*>(base + ws.acc_off);
@@ -893,8 +937,11 @@ int launch_decode(const vtc_attn_params& p, int32_t num_seqs, const void* q, con
                   const void* v_cache, const int32_t* block_table, const int32_t* seq_lens, void* out,
                   void* workspace, int32_t max_waves, hipStream_t stream, hipEvent_t ev_begin, hipEvent_t ev_end,
                   const CounterJob& job) {
-  // the flattened block index must fit the 64-bit products used above and the grid limits of the merge launch
-  if ((long long)num_seqs * p.max_blocks_per_seq >= (1ll << 31)) return VTC_ERR_UNSUPPORTED;
+  // the batch's cost units per kv head, and one sequence's over all kv heads, must fit 31 bits (the plan's prefixes
+  // and offsets are 32-bit)
+  if ((long long)num_seqs * ((long long)p.max_blocks_per_seq + kPieceUnits) >= (1ll << 31) ||
+      ((long long)p.max_blocks_per_seq + kPieceUnits) * p.num_kv_heads >= (1ll << 31))
+    return VTC_ERR_UNSUPPORTED;
   if (p.dtype == VTC_F16)
     return launch_group<F16>(p, num_seqs, q, k_cache, v_cache, block_table, seq_lens, out, workspace, max_waves, stream,
                              ev_begin, ev_end, job);

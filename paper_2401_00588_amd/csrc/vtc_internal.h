@@ -23,14 +23,15 @@ constexpr float kLog2e = 1.4426950408889634f;
 constexpr int kDecodeWavesPerCuMha = 8;      // num_q_heads == num_kv_heads (vector-ALU engine)
 constexpr int kDecodeWavesPerCuGqa = 4;      // grouped queries (matrix-core engine)
 constexpr int kMaxDecodeWaves = 8192;        // upper bound on the launch on any device
-constexpr int kMinBlocksPerWave = 2;         // small batches use fewer waves rather than shorter ranges
+constexpr int kPieceUnits = 1;               // cost of beginning a (sequence, kv head), in units of one KV block
+constexpr int kMinUnitsPerWave = 1 + kPieceUnits;   // a range of that many units holds at least one block: small batches use fewer waves
 
 // One fp32 partial result of a piece: running max m (log2 domain), sum l, acc[128].
 constexpr int kPartialFloats = kHeadDim;
 
 // Written by the planning kernel (or by wave 0 of a self-planning launch), read by the merge kernel.
 struct DecodeHeader {
-  long long gtot;   // KV blocks in the stream: (sum over sequences of blocks) * num_kv_heads
+  long long gtot;   // cost units in the stream: (sum over non-empty sequences of blocks + kPieceUnits) * num_kv_heads
   long long quot;   // gtot / waves
   int rem;          // gtot % waves
   int waves;        // waves that received a non-empty range
@@ -116,7 +117,7 @@ __device__ __forceinline__ float fast_exp2(float x) { return __builtin_amdgcn_ex
 // ---- host side --------------------------------------------------------------
 struct DecodeWorkspace {
   size_t header_off;        // DecodeHeader
-  size_t seg_prefix_off;    // int32 [num_seqs + 1]      exclusive prefix of KV blocks per sequence
+  size_t seg_prefix_off;    // uint64[num_seqs + 1]      exclusive prefix per sequence: non-empty sequences << 32 | KV blocks
   size_t wave_desc_off;     // int4  [max(waves, 64)]    (r, h, b, n_blocks): start and length of a wave's range
   size_t ml_off;            // float2[2 * waves * G]     (m, l) of each partial piece
   size_t acc_off;           // float [2 * waves * G * 128]
@@ -149,7 +150,7 @@ inline DecodeWorkspace decode_workspace_layout(const vtc_attn_params& p, int32_t
   ws.header_off = at;
   at = 256;
   ws.seg_prefix_off = at;
-  at = align_up(at + sizeof(int32_t) * ((size_t)num_seqs + 1), 256);
+  at = align_up(at + sizeof(uint64_t) * ((size_t)num_seqs + 1), 256);
   ws.wave_desc_off = at;
   at = align_up(at + sizeof(int32_t) * 4 * (w > 64 ? w : 64), 256);    // at least 1 KiB: also the target of dummy prefetches
   ws.ml_off = at;
@@ -161,12 +162,13 @@ inline DecodeWorkspace decode_workspace_layout(const vtc_attn_params& p, int32_t
 }
 
 // Waves that a launch over sequences of at most max_seq_len tokens can put to use (0 or less: the block
-// table's capacity): every wave gets at least kMinBlocksPerWave KV blocks.
+// table's capacity): every wave gets at least kMinUnitsPerWave cost units of the batch, a unit being a KV block
+// or the start of a (sequence, kv head).
 inline int decode_waves_for(const vtc_attn_params& p, int32_t num_seqs, int32_t max_seq_len) {
   const long long cap = (long long)p.max_blocks_per_seq;
   long long nb = max_seq_len > 0 ? ((long long)max_seq_len + p.block_size - 1) / p.block_size : cap;
   if (nb > cap) nb = cap;
-  const long long want = (nb * num_seqs * p.num_kv_heads + kMinBlocksPerWave - 1) / kMinBlocksPerWave;
+  const long long want = (nb + kPieceUnits) * num_seqs * p.num_kv_heads / kMinUnitsPerWave;
   const long long bound = decode_wave_bound(p);
   const long long w = want < bound ? want : bound;
   return (int)(w > 1 ? w : 1);

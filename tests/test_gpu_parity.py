@@ -160,7 +160,7 @@ def test_decode_of_a_batch_with_no_tokens_at_all(torch, n):
 
 @pytest.mark.parametrize("n,hq,hkv,dtype", [(2500, 4, 2, "bf16"), (9000, 2, 2, "f16")])
 def test_decode_many_short_sequences(torch, n, hq, hkv, dtype):
-    # more sequences than one planning pass (1024) and than the planner's on-chip prefix table (8192) hold;
+    # more sequences than one planning pass (1024) and than the planner's on-chip prefix table (4096) hold;
     # many ranges then span several whole sequences, some of them empty
     say(f"decode {n} short sequences dtype={dtype}")
     rng = np.random.default_rng(n)
@@ -170,6 +170,19 @@ def test_decode_many_short_sequences(torch, n, hq, hkv, dtype):
     err = np.abs(got - want).max()
     say(f"  max abs err {err:.3e}")
     assert (got[seq == 0] == 0).all()
+
+
+@pytest.mark.parametrize("seq,hq,hkv,dtype", [([1], 8, 8, "f16"), ([16, 1, 33, 0, 2], 8, 2, "bf16"),
+                                              ([5] * 40, 32, 8, "bf16"), ([17, 16, 15] * 9, 4, 4, "f16"),
+                                              ([1, 0, 0, 1, 0, 2000, 1, 1], 32, 32, "f16")])
+def test_decode_ranges_of_a_block_or_two(torch, seq, hq, hkv, dtype):
+    # The stream is cut by cost -- a block is one unit, beginning a (sequence, kv head) another -- and a batch this
+    # small gets ranges of two or three units: a head's beginning plus its only block, the last block of one head
+    # plus the beginning of the next, and cuts that fall on a beginning.  The long sequence of the last case is cut
+    # into many ranges while its neighbours are one block each.
+    say(f"decode tiny ranges {seq[:8]}... dtype={dtype} Hq={hq} Hkv={hkv}")
+    got, want = _decode_case(torch, seq, hq, hkv, dtype, seed=900 + len(seq))
+    assert (got[np.asarray(seq) == 0] == 0).all()
 
 
 @pytest.mark.parametrize("n", [1, 63, 64, 65, 130, 1000, 1024, 1025])
