@@ -814,16 +814,19 @@ __global__ __launch_bounds__(kWave * G) void decode_merge_kernel(const DecodeHea
 
 // ---------------------------------------------------- general block size ----
 // KV blocks of fewer than 16 tokens (the paper's own system pages its cache one token at a time, Section 5.1).
-// One wave per query row -- a (sequence, query head) of a decode step, or a (chunk token, query head) of a prefill
-// chunk with its causal limit -- gathers 16 tokens at a time through the block table, whatever the block size,
-// and hands them to the vector-ALU engine of the tuned decode kernel.  No workspace; correctness path, not tuned.
-template <typename T>
+// One wave per (sequence, kv head) of a decode step, or per (chunk token, kv head) of a prefill chunk with its
+// causal limit, gathers 16 tokens at a time through the block table, whatever the block size, and hands them to
+// the vector-ALU engine of the tuned decode kernel for the G query heads of the group at once (so K and V are
+// read once, not once per query head).  No workspace; not tuned beyond that (measured on 256 / 512-sequence
+// batches like cfg3 / cfg4: 5.2-5.4 TB/s with one query head per KV head against 6.5 through 16-token blocks).
+template <typename T, int G>
 __global__ __launch_bounds__(kWave) void attend_general_kernel(
     const uint16_t* __restrict__ q, const int32_t* __restrict__ cu_q_lens, const uint16_t* __restrict__ k_cache,
     const uint16_t* __restrict__ v_cache, const int32_t* __restrict__ block_table,
-    const int32_t* __restrict__ seq_lens, void* __restrict__ out, int32_t out_f32, int32_t num_q_heads,
-    int32_t num_kv_heads, int32_t max_blocks_per_seq, int32_t block_size, float scale2) {
-  const int r = blockIdx.z, h = blockIdx.y, lane = threadIdx.x;
+    const int32_t* __restrict__ seq_lens, void* __restrict__ out, int32_t out_f32, int32_t num_kv_heads,
+    int32_t max_blocks_per_seq, int32_t block_size, float scale2) {
+  const int r = blockIdx.z, kv_head = blockIdx.y, lane = threadIdx.x;
+  const int num_q_heads = num_kv_heads * G;
   const int s_len = min(max(seq_lens[r], 0), max_blocks_per_seq * block_size);
   int q_row = r, n_keys = s_len;                       // decode: every cached token is visible
   if (cu_q_lens != nullptr) {                          // prefill chunk: token i at position s_len - lq + i sees keys 0 .. position
@@ -833,18 +836,17 @@ __global__ __launch_bounds__(kWave) void attend_general_kernel(
     q_row = q_begin + blockIdx.x;
     n_keys = s_len < lq ? 0 : s_len - lq + (int)blockIdx.x + 1;     // a context shorter than its chunk: zero rows
   }
-  const size_t row_elems = ((size_t)q_row * num_q_heads + h) * kHeadDim;
-  void* const out_row = static_cast<char*>(out) + row_elems * (out_f32 ? 4 : 2);
+  const size_t row_elems = ((size_t)q_row * num_q_heads + kv_head * G) * kHeadDim;     // G consecutive rows
+  void* const out_rows = static_cast<char*>(out) + row_elems * (out_f32 ? 4 : 2);
   if (n_keys == 0) {
-    uint32_t* dst = static_cast<uint32_t*>(out_row);
-    for (int i = lane; i < (out_f32 ? kHeadDim : kHeadDim / 2); i += kWave) dst[i] = 0u;
+    uint32_t* dst = static_cast<uint32_t*>(out_rows);
+    for (int i = lane; i < G * (out_f32 ? kHeadDim : kHeadDim / 2); i += kWave) dst[i] = 0u;
     return;
   }
-  ValuEngine<T, 1> eng;
+  ValuEngine<T, G> eng;
   eng.init(lane, nullptr);
-  u32x4 qreg[1], k[4], v[4];
+  u32x4 qreg[G], k[4], v[4];
   eng.load_q(qreg, q + row_elems);
-  const int kv_head = h / (num_q_heads / num_kv_heads);
   const int32_t* __restrict__ table = block_table + (size_t)r * max_blocks_per_seq;
   for (int j0 = 0; j0 < n_keys; j0 += kBlockSize) {
 #pragma unroll
@@ -856,22 +858,39 @@ __global__ __launch_bounds__(kWave) void attend_general_kernel(
     }
     eng.block(qreg, k, v, scale2, min(kBlockSize, n_keys - j0));
   }
-  eng.finish(true, PieceSink{out_row, out_f32 != 0, nullptr, nullptr});
+  eng.finish(true, PieceSink{out_rows, out_f32 != 0, nullptr, nullptr});
+}
+
+template <typename T>
+static int launch_general_typed(const vtc_attn_params& p, int32_t num_seqs, const void* q, const int32_t* cu_q_lens,
+                                int32_t max_q_len, const void* k_cache, const void* v_cache,
+                                const int32_t* block_table, const int32_t* seq_lens, void* out, hipStream_t stream) {
+  const dim3 grid(cu_q_lens ? max_q_len : 1, p.num_kv_heads, num_seqs);
+  auto go = [&](auto kernel) {
+    hipLaunchKernelGGL(kernel, grid, dim3(kWave), 0, stream, static_cast<const uint16_t*>(q), cu_q_lens,
+                       static_cast<const uint16_t*>(k_cache), static_cast<const uint16_t*>(v_cache), block_table,
+                       seq_lens, out, p.out_dtype == VTC_F32 ? 1 : 0, p.num_kv_heads, p.max_blocks_per_seq,
+                       p.block_size, p.scale * kLog2e);
+  };
+  switch (p.num_q_heads / p.num_kv_heads) {
+    case 1: go(attend_general_kernel<T, 1>); break;
+    case 2: go(attend_general_kernel<T, 2>); break;
+    case 4: go(attend_general_kernel<T, 4>); break;
+    case 8: go(attend_general_kernel<T, 8>); break;
+    default: return VTC_ERR_UNSUPPORTED;
+  }
+  return hipGetLastError() == hipSuccess ? VTC_OK : VTC_ERR_HIP;
 }
 
 int launch_attend_general(const vtc_attn_params& p, int32_t num_seqs, const void* q, const int32_t* cu_q_lens,
                           int32_t max_q_len, const void* k_cache, const void* v_cache, const int32_t* block_table,
                           const int32_t* seq_lens, void* out, hipStream_t stream) {
-  if (num_seqs > 65535 || p.num_q_heads > 65535) return VTC_ERR_UNSUPPORTED;
-  const dim3 grid(cu_q_lens ? max_q_len : 1, p.num_q_heads, num_seqs);
-  auto go = [&](auto kernel) {
-    hipLaunchKernelGGL(kernel, grid, dim3(kWave), 0, stream, static_cast<const uint16_t*>(q), cu_q_lens,
-                       static_cast<const uint16_t*>(k_cache), static_cast<const uint16_t*>(v_cache), block_table,
-                       seq_lens, out, p.out_dtype == VTC_F32 ? 1 : 0, p.num_q_heads, p.num_kv_heads,
-                       p.max_blocks_per_seq, p.block_size, p.scale * kLog2e);
-  };
-  if (p.dtype == VTC_F16) go(attend_general_kernel<F16>); else go(attend_general_kernel<BF16>);
-  return hipGetLastError() == hipSuccess ? VTC_OK : VTC_ERR_HIP;
+  if (num_seqs > 65535 || p.num_kv_heads > 65535) return VTC_ERR_UNSUPPORTED;      // grid limits
+  if (p.dtype == VTC_F16)
+    return launch_general_typed<F16>(p, num_seqs, q, cu_q_lens, max_q_len, k_cache, v_cache, block_table, seq_lens, out,
+                                     stream);
+  return launch_general_typed<BF16>(p, num_seqs, q, cu_q_lens, max_q_len, k_cache, v_cache, block_table, seq_lens, out,
+                                    stream);
 }
 
 // -------------------------------------------------------------- launcher ----
