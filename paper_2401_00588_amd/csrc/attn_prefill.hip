@@ -309,7 +309,16 @@ __global__ __launch_bounds__(kPfThreads, 2) void prefill_chunk_kernel(
       for (int sb = 0; sb < 2; ++sb)
 #pragma unroll
         for (int v = 0; v < 16; ++v) mx = fmaxf(mx, kPosScale ? sacc[sb][v] : -sacc[sb][v]);
-      mx = fmaxf(mx, __shfl_xor(mx, 32));
+      {
+        // The other half of the row's keys sits 32 lanes away.  v_permlane32_swap exchanges lanes 32..63 of its first
+        // operand with lanes 0..31 of its second, so with the row maximum in both, every lane finds its own half in
+        // one and the other half in the other: a vector instruction instead of an LDS round trip in the middle of the
+        // tile's dependency chain.  (Inline assembly: through the builtin this compiler hands out the first result
+        // register for both results.)
+        uint32_t mx_a = __builtin_bit_cast(uint32_t, mx), mx_b = mx_a;
+        asm volatile("s_nop 1\n\tv_permlane32_swap_b32 %0, %1\n\ts_nop 1" : "+v"(mx_a), "+v"(mx_b));
+        mx = fmaxf(__builtin_bit_cast(float, mx_a), __builtin_bit_cast(float, mx_b));
+      }
       const float m_tile = mx * (kPosScale ? scale2 : -scale2);     // = max of the scaled logits, or -inf
       // The reference exponent follows the maximum only when that has grown by more than 8 since it last moved,
       // so weights stay <= 2^8 (exact in either storage type's range) and the 64 accumulators are rescaled once or
