@@ -17,10 +17,12 @@
 //   attend  one 64-lane wave per range.  The wave walks its range block by block,
 //           always one block of loads ahead of the arithmetic, across sequence and
 //           head boundaries without draining.  Each maximal run of blocks of one
-//           (r, h) inside the range is a *piece*; when a piece ends the wave writes
-//           either the final output (the piece is the whole sequence) or an fp32
-//           partial (m, l, acc[128] per q head).  A wave owns at most two partial
-//           pieces: one cut at its range start and one cut at its range end.
+//           (r, h) inside the range is a *piece*; a piece that ends becomes either the
+//           final output (the piece is the whole sequence) or an fp32 partial
+//           (m, l, acc[128] per q head).  A wave owns at most two partial pieces: one
+//           cut at its range start and one cut at its range end.  Closed pieces wait
+//           in an LDS patch and leave for global memory together, few instructions
+//           for many rows, when the patch is full or the range ends.
 //   merge   one wave per range boundary: if the boundary cuts a (r, h), combines the
 //           partials of the waves that share it exactly (rescale by exp2(m_c - m))
 //           and writes the output; also writes zeros for empty sequences.  When the
@@ -286,6 +288,83 @@ __device__ __forceinline__ void load_tile(u32x4 (&dst)[4], const uint16_t* __res
   }
 }
 
+// Pieces a wave has closed are parked in LDS and written to global memory together, when the patch is full or the
+// range ends, with as few store instructions as their bytes allow.  In this kernel a store instruction costs a wave
+// 0.3-0.8 us whatever it carries (the memory pipeline is full of the other waves' loads; measured on batches of the
+// same bytes in 4 x as many sequences with and without the stores), and stores issued between a tile's loads and
+// their wait also make that wait cover their completion (the compiler cannot count stores that only some
+// iterations issue).  A lane of a store can write anywhere, so one instruction carries the 16-bit output rows of
+// four (sequence, query head) pairs, or two fp32 rows, or every parked partial's (m, l).
+// A parked piece: for each of the group's G query heads 128 unnormalised fp32 sums, the running maximum m and the
+// sum l (kParkFloats apart, 16-byte aligned), then the descriptor.
+constexpr int kParkFloats = kHeadDim + 4;
+struct ParkedPiece {
+  uint32_t whole;        // 1: the piece is a whole (sequence, kv head): normalise and write the output rows
+  uint32_t slot0;        // 0: write partial slots slot0 .. slot0 + G - 1
+  uint32_t out_row_lo;   // element offset of the first of the G output rows
+  uint32_t out_row_hi;
+};
+template <int G>
+constexpr int park_stride() { return G * kParkFloats + 4; }     // in 4-byte words
+
+// Write n parked pieces out.  Their n * G rows (at most 64) are taken four (16-bit output) or two (fp32 output,
+// partial sums) at a time; a lane whose row is of the other kind stays idle.
+template <typename T, int G>
+__device__ __forceinline__ void flush_pieces(const float* __restrict__ parked, int n, int lane, void* __restrict__ out,
+                                             int32_t out_f32, float2* __restrict__ part_ml,
+                                             float* __restrict__ part_acc) {
+  using f32x4 = float __attribute__((ext_vector_type(4)));
+  const int rows = n * G;
+  auto row_of = [&](int rho, const float*& row, u32x4& d) {      // rho < rows
+    const int pi = rho / G, g = rho % G;
+    const float* piece = parked + pi * park_stride<G>();
+    row = piece + g * kParkFloats;
+    d = *reinterpret_cast<const u32x4*>(piece + G * kParkFloats);
+    return g;
+  };
+  if (!out_f32) {
+    for (int base = 0; base < rows; base += 4) {                 // 16 lanes x 8 dims per row
+      const int rho = base + (lane >> 4), chunk = lane & 15;
+      if (rho < rows) {
+        const float* row;
+        u32x4 d;
+        const int g = row_of(rho, row, d);
+        if (d[0] != 0u) {
+          const f32x4 a0 = *reinterpret_cast<const f32x4*>(row + chunk * 8);
+          const f32x4 a1 = *reinterpret_cast<const f32x4*>(row + chunk * 8 + 4);
+          const float inv = 1.f / row[kHeadDim + 1];
+          const u32x4 o = u32x4{pack2<T>(a0[0] * inv, a0[1] * inv), pack2<T>(a0[2] * inv, a0[3] * inv),
+                                pack2<T>(a1[0] * inv, a1[1] * inv), pack2<T>(a1[2] * inv, a1[3] * inv)};
+          const size_t at = ((size_t)d[2] | ((size_t)d[3] << 32)) + (size_t)g * kHeadDim + chunk * 8;
+          *reinterpret_cast<u32x4*>(static_cast<uint16_t*>(out) + at) = o;
+        }
+      }
+    }
+  }
+  for (int base = 0; base < rows; base += 2) {                   // 32 lanes x 4 dims per row
+    const int rho = base + (lane >> 5), chunk = lane & 31;
+    if (rho < rows) {
+      const float* row;
+      u32x4 d;
+      const int g = row_of(rho, row, d);
+      const f32x4 a = *reinterpret_cast<const f32x4*>(row + chunk * 4);
+      if (d[0] == 0u) {
+        *reinterpret_cast<f32x4*>(part_acc + (size_t)(d[1] + g) * kPartialFloats + chunk * 4) = a;
+      } else if (out_f32) {
+        const float inv = 1.f / row[kHeadDim + 1];
+        const size_t at = ((size_t)d[2] | ((size_t)d[3] << 32)) + (size_t)g * kHeadDim + chunk * 4;
+        *reinterpret_cast<f32x4*>(static_cast<float*>(out) + at) = f32x4{a[0] * inv, a[1] * inv, a[2] * inv, a[3] * inv};
+      }
+    }
+  }
+  if (lane < rows) {                                              // the partials' (m, l): one instruction for all
+    const float* row;
+    u32x4 d;
+    const int g = row_of(lane, row, d);
+    if (d[0] == 0u) part_ml[d[1] + g] = *reinterpret_cast<const float2*>(row + kHeadDim);
+  }
+}
+
 // Where a finished piece goes: the output row block of its (sequence, kv head) and its partial slot.
 struct PieceSink {
   void* out_rows;       // G consecutive output rows of 128 (of the storage type, or fp32 when out_f32)
@@ -301,6 +380,7 @@ struct ValuEngine {
   static constexpr int kLdsElems = 0;
   static constexpr int kMinWavesPerSimd = G == 1 ? 4 : (G == 2 ? 3 : (G == 4 ? 2 : 1));   // register budget (used with G = 1)
   static constexpr int kWavesPerCu = kDecodeWavesPerCuMha;
+  static constexpr int kParked = 16;                // pieces parked in LDS before they are written out (8.3 KiB)
   int row, sub;
   float m[G];        // running max of the scaled logits (log2 domain), per 16-lane row
   float l[G];        // running sum of exp2(logit - m)
@@ -388,8 +468,8 @@ struct ValuEngine {
       block_t<false>(q, k, v, scale2, kBlockSize);
   }
 
-  // Close a piece: merge the four 16-lane rows, write the output (whole sequence) or a partial, reset.
-  __device__ __forceinline__ void finish(bool whole, const PieceSink& sink) {
+  // Merge the four 16-lane rows of the softmax state (the result is complete in the lanes of row 0).
+  __device__ __forceinline__ void merge_rows() {
 #pragma unroll
     for (int off = 16; off <= 32; off <<= 1) {
 #pragma unroll
@@ -406,6 +486,24 @@ struct ValuEngine {
         m[g] = m_n;
       }
     }
+  }
+  // Close a piece into an LDS patch (see ParkedPiece) and reset.
+  __device__ __forceinline__ void park(float* piece) {
+    merge_rows();
+    if (row == 0) {
+#pragma unroll
+      for (int g = 0; g < G; ++g) {
+        float4* dst = reinterpret_cast<float4*>(piece + g * kParkFloats + sub * 8);
+        dst[0] = make_float4(acc[g][0], acc[g][1], acc[g][2], acc[g][3]);
+        dst[1] = make_float4(acc[g][4], acc[g][5], acc[g][6], acc[g][7]);
+        if (sub == 0) *reinterpret_cast<float2*>(piece + g * kParkFloats + kHeadDim) = make_float2(m[g], l[g]);
+      }
+    }
+    reset();
+  }
+  // Close a piece: merge the four 16-lane rows, write the output (whole sequence) or a partial, reset.
+  __device__ __forceinline__ void finish(bool whole, const PieceSink& sink) {
+    merge_rows();
     if (row == 0) {
 #pragma unroll
       for (int g = 0; g < G; ++g) {
@@ -453,6 +551,7 @@ struct MfmaEngine {
   static constexpr int kLdsElems = kBlockSize * (kPitchK + kPitchV) + 4 * kQRegs * kPitchQ;
   static constexpr int kMinWavesPerSimd = 2;      // register budget = 512 / this (three waves spill)
   static constexpr int kWavesPerCu = kDecodeWavesPerCuGqa;
+  static constexpr int kParked = G <= 2 ? 8 : 24 / G;   // pieces parked in LDS before they are written out (12.5 KiB)
   using f32x4 = float __attribute__((ext_vector_type(4)));
   using f16x8 = _Float16 __attribute__((ext_vector_type(8)));
   using bf16x8 = __bf16 __attribute__((ext_vector_type(8)));
@@ -571,6 +670,18 @@ struct MfmaEngine {
     }
   }
 
+  // Close a piece into an LDS patch (see ParkedPiece) and reset.
+  __device__ __forceinline__ void park(float* piece) {
+    float l_tot = l + __shfl_xor(l, 16);
+    l_tot += __shfl_xor(l_tot, 32);
+    if (j < G) {
+      float* dst = piece + j * kParkFloats + 4 * kg;
+#pragma unroll
+      for (int db = 0; db < 8; ++db) *reinterpret_cast<f32x4*>(dst + db * 16) = acc[db];
+      if (kg == 0) *reinterpret_cast<float2*>(piece + j * kParkFloats + kHeadDim) = make_float2(m, l_tot);
+    }
+    reset();
+  }
   __device__ __forceinline__ void finish(bool whole, const PieceSink& sink) {
     float l_tot = l + __shfl_xor(l, 16);
     l_tot += __shfl_xor(l_tot, 32);
@@ -620,6 +731,7 @@ __global__ __launch_bounds__(kWave, Engine::kMinWavesPerSimd) void decode_attend
     DecodeHeader* __restrict__ header) {
   constexpr int kQRegs = Engine::kQRegs;
   __shared__ __attribute__((aligned(16))) uint16_t lds[Engine::kLdsElems > 0 ? Engine::kLdsElems : 8];
+  __shared__ __attribute__((aligned(16))) float parked[Engine::kParked * park_stride<G>()];
   const int lane = threadIdx.x;
   const int num_q_heads = num_kv_heads * G;
   const int max_tokens = max_blocks_per_seq * kBlockSize;
@@ -687,6 +799,11 @@ __global__ __launch_bounds__(kWave, Engine::kMinWavesPerSimd) void decode_attend
   // where the prefetch goes when there is no next block: 1 KiB of the (cache-resident) range table
   const uint16_t* const dummy = reinterpret_cast<const uint16_t*>(wave_desc);
 
+  int n_parked = 0;                        // pieces closed and not yet written out
+  auto flush_parked = [&]() {
+    flush_pieces<T, G>(parked, n_parked, lane, out, out_f32, part_ml, part_acc);
+    n_parked = 0;
+  };
   // Consume the block at `cur` from (qreg, kx, vx); close the piece if it ends here.
   auto consume = [&](const u32x4 (&qreg)[kQRegs], u32x4 (&kx)[4], u32x4 (&vx)[4], bool last_of_range) {
     const bool last_of_seq = cur.b + 1 == cur.nb;
@@ -694,11 +811,20 @@ __global__ __launch_bounds__(kWave, Engine::kMinWavesPerSimd) void decode_attend
     eng.block(qreg, kx, vx, scale2, nvalid);
     if (!(last_of_seq || last_of_range)) return;
     const bool whole = piece_lo == 0 && last_of_seq;     // the piece is the entire sequence
-    // partial slot 0: the piece cut at the start of this wave's range; slot 1: the one cut at its end
-    const size_t slot0 = ((size_t)wave * 2 + (piece_lo == 0 ? 1 : 0)) * G;
-    const size_t out_row = ((size_t)cur.r * num_q_heads + cur.h * G) * kHeadDim;      // in elements
-    eng.finish(whole, PieceSink{static_cast<char*>(out) + out_row * (out_f32 ? 4 : 2), out_f32 != 0,
-                                part_acc + slot0 * kPartialFloats, part_ml + slot0});
+    if (n_parked == Engine::kParked) flush_parked();
+    float* piece = parked + n_parked * park_stride<G>();
+    eng.park(piece);
+    if (lane == 0) {
+      // partial slot 0: the piece cut at the start of this wave's range; slot 1: the one cut at its end
+      const size_t out_row = ((size_t)cur.r * num_q_heads + cur.h * G) * kHeadDim;      // in elements
+      ParkedPiece d;
+      d.whole = whole ? 1u : 0u;
+      d.slot0 = (uint32_t)((wave * 2 + (piece_lo == 0 ? 1 : 0)) * G);
+      d.out_row_lo = (uint32_t)out_row;
+      d.out_row_hi = (uint32_t)(out_row >> 32);
+      *reinterpret_cast<ParkedPiece*>(piece + G * kParkFloats) = d;
+    }
+    ++n_parked;
     piece_lo = 0;                           // a new (r, h) starts with the next block
   };
 
@@ -734,6 +860,7 @@ __global__ __launch_bounds__(kWave, Engine::kMinWavesPerSimd) void decode_attend
     nxt = far;
     if (i + 2 < n_blocks) step(far);
   }
+  flush_parked();                          // nothing waits for these stores any more
 }
 
 // ----------------------------------------------------------------- merge ----
