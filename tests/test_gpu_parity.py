@@ -104,7 +104,8 @@ def test_gathered_slots_are_bit_exact(torch):
 
 
 # -------------------------------------------------------------------- decode
-def _decode_case(torch, seq_lens, hq, hkv, dtype, seed, poison=False, min_row_len=0, scale=SCALE, label="decode"):
+def _decode_case(torch, seq_lens, hq, hkv, dtype, seed, poison=False, min_row_len=0, scale=SCALE, label="decode",
+                 workspace_bytes=None):
     """One decode call with 16-bit and one with fp32 output rows, both checked against the oracle."""
     rng = np.random.default_rng(seed)
     table, nb = make_block_table(rng, seq_lens, 16, min_row_len=min_row_len)
@@ -114,8 +115,11 @@ def _decode_case(torch, seq_lens, hq, hkv, dtype, seed, poison=False, min_row_le
         poison_unused_rows(v, table, seq_lens, NAN_BITS[dtype])
     args = (bits_to_tensor(q, dtype), bits_to_tensor(k, dtype), bits_to_tensor(v, dtype), _i32(torch, table),
             _i32(torch, seq_lens))
-    out16 = vtc.vtc_attn_decode(vtc.make_params(hq, hkv, 128, 16, table.shape[1], dtype, scale), *args)
-    out32 = vtc.vtc_attn_decode(vtc.make_params(hq, hkv, 128, 16, table.shape[1], dtype, scale, "f32"), *args)
+    kw = {}
+    if workspace_bytes is not None:
+        kw["workspace"] = torch.empty(workspace_bytes, dtype=torch.uint8, device="cuda")
+    out16 = vtc.vtc_attn_decode(vtc.make_params(hq, hkv, 128, 16, table.shape[1], dtype, scale), *args, **kw)
+    out32 = vtc.vtc_attn_decode(vtc.make_params(hq, hkv, 128, 16, table.shape[1], dtype, scale, "f32"), *args, **kw)
     torch.cuda.synchronize()
     want = OA.paged_decode(q, k, v, table, seq_lens, scale, dtype)
     got = check_both_outputs(out16, out32, want, dtype, label)
@@ -169,6 +173,25 @@ def test_decode_many_short_sequences(torch, n, hq, hkv, dtype):
     got, want = _decode_case(torch, seq, hq, hkv, dtype, seed=n + 1)
     err = np.abs(got - want).max()
     say(f"  max abs err {err:.3e}")
+    assert (got[seq == 0] == 0).all()
+
+
+@pytest.mark.parametrize("dtype,hq,hkv", [("f16", 4, 4), ("bf16", 8, 2), ("bf16", 32, 8), ("f16", 16, 2)])
+def test_decode_with_a_workspace_for_a_few_waves(torch, dtype, hq, hkv):
+    # A workspace with room for about one wave per KV head: the call runs on that few waves, every one of them
+    # closes hundreds of (sequence, kv head) pieces -- far more than it can park in LDS before writing them out --
+    # and the long sequences are cut by several ranges.  Same results as with any other number of waves.
+    say(f"decode on a few waves dtype={dtype} Hq={hq} Hkv={hkv}")
+    rng = np.random.default_rng(77)
+    n = 300
+    seq = rng.integers(0, 41, size=n).astype(np.int32)
+    seq[rng.integers(0, n, size=4)] = 333
+    table_cols = (int(seq.max()) + 15) // 16
+    p = vtc.make_params(hq, hkv, 128, 16, table_cols, dtype, SCALE)
+    # sized for a single one-block sequence (one wave per KV head) plus this batch's per-sequence prefix
+    small = vtc.vtc_attn_workspace_bytes(p, 1, 1) + 8 * n + 256
+    assert small < vtc.vtc_attn_workspace_bytes(p, n, 0) // 8
+    got, want = _decode_case(torch, seq, hq, hkv, dtype, seed=78, workspace_bytes=small)
     assert (got[seq == 0] == 0).all()
 
 
