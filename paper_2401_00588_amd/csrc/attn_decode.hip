@@ -169,6 +169,20 @@ __global__ __launch_bounds__(kPlanThreads) void decode_plan_kernel(const int32_t
   }
 }
 
+// Inclusive prefix sum over the 64 lanes with data-parallel-primitive moves (vector instructions; a shuffle-based
+// scan is six dependent LDS round trips, and every wave of a self-planning launch runs two of them before its first
+// load): shifts by 1, 2, 4, 8 inside the 16-lane rows, then row 0's total into row 1 and row 2's into row 3, then
+// the first half's total into the second.  Lanes without a source add 0.
+__device__ __forceinline__ int wave_inclusive_sum(int x) {
+  x += __builtin_amdgcn_update_dpp(0, x, 0x111, 0xf, 0xf, false);      // row_shr:1
+  x += __builtin_amdgcn_update_dpp(0, x, 0x112, 0xf, 0xf, false);      // row_shr:2
+  x += __builtin_amdgcn_update_dpp(0, x, 0x114, 0xf, 0xf, false);      // row_shr:4
+  x += __builtin_amdgcn_update_dpp(0, x, 0x118, 0xf, 0xf, false);      // row_shr:8
+  x += __builtin_amdgcn_update_dpp(0, x, 0x142, 0xa, 0xf, false);      // row_bcast:15 into rows 1 and 3
+  x += __builtin_amdgcn_update_dpp(0, x, 0x143, 0xc, 0xf, false);      // row_bcast:31 into rows 2 and 3
+  return x;
+}
+
 // ------------------------------------------------------------- self-plan ----
 // The same plan without a launch, for batches of at most 64 x 16 sequences: every wave computes
 // the prefix in registers (lane i holds sequences i*c .. i*c+c-1, c = ceil(N / 64)) and looks
@@ -216,15 +230,7 @@ __device__ __forceinline__ int4 self_plan(const int32_t* __restrict__ seq_lens, 
     mine_b += nbv[j];
     mine_s += nbv[j] > 0 ? 1 : 0;
   }
-  int incl_b = mine_b, incl_s = mine_s;
-#pragma unroll
-  for (int off = 1; off < kWave; off <<= 1) {
-    const int yb = __shfl_up(incl_b, off), ys = __shfl_up(incl_s, off);
-    if (lane >= off) {
-      incl_b += yb;
-      incl_s += ys;
-    }
-  }
+  const int incl_b = wave_inclusive_sum(mine_b), incl_s = wave_inclusive_sum(mine_s);
   const int total_blocks = __builtin_amdgcn_readlane(incl_b, kWave - 1);
   const int total_seqs = __builtin_amdgcn_readlane(incl_s, kWave - 1);
   const int excl_b = incl_b - mine_b, excl_s = incl_s - mine_s;      // of all sequences before this lane's
