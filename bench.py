@@ -37,7 +37,7 @@ EVENT_EVERY = 5                # steps between two kernel-level HIP event pairs
 # by the copy-kernel calibration (profiles/decode_attend_cfg3_hbm_bytes.md).  Valid only for the kernel
 # source the counters were taken with: keyed by the SHA-256 of the two files that define that kernel.
 DECODE_TRAFFIC_CFG3 = {
-    "d3f2bc7c0f1564f7": 4060149289,
+    "c4da850657273659": 4060144550,
 }
 
 
