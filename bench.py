@@ -276,9 +276,15 @@ def prefill_kernel_on_cfg5(torch, vtc, chunk, launches=24, reps=5, rotate=6):
     per_launch.sort()
     ms = per_launch[len(per_launch) // 2]
     tf = batch.prefill_flops / ms / 1e9
+    # the bytes that must cross HBM at least once: q rows in, output rows out, K and V of every sequence's context
+    esz = 2
+    hbm_bytes = (2 * n * lq * sh.num_q_heads + 2 * n * s_len * sh.num_kv_heads) * sh.head_dim * esz
     return {"kernel": "prefill_chunk_kernel", "chunk": chunk, "flops": batch.prefill_flops, "dtype": sh.dtype,
             "ms_per_launch": round(ms, 5), "ms_per_launch_min": round(per_launch[0], 5), "achieved": round(tf, 1),
             "unit": "TFLOP/s", "frac": round(tf / MFMA_PEAK_TFLOPS, 4),
+            "hbm_bytes": hbm_bytes, "hbm_gbs": round(hbm_bytes / ms / 1e6, 1),
+            "hbm_frac": round(hbm_bytes / ms / 1e6 / HBM_PEAK_GBS, 4),
+            "flop_per_byte": round(batch.prefill_flops / hbm_bytes, 1),
             "method": f"{launches} back-to-back launches over {rotate} distinct input sets per event pair"}
 
 
