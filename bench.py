@@ -39,6 +39,16 @@ EVENT_EVERY = 5                # steps between two kernel-level HIP event pairs
 DECODE_TRAFFIC_CFG3 = {
     "c4da850657273659": 4060144550,
 }
+# The same counters for the decode kernel on cfg4 / cfg5 and for the prefill kernel on the two cfg5 chunks
+# (profiles/decode_attend_cfg4_kernel_trace.md, profiles/mixed_step_cfg5_kernel_trace.md).
+DECODE_TRAFFIC_OTHER = {
+    4: {"c4da850657273659": 1169578684},
+    5: {"c4da850657273659": 2108728181},
+}
+PREFILL_TRAFFIC_CFG5 = {
+    0: {"20a71fd2a92a36be": 84122384},
+    1: {"20a71fd2a92a36be": 100899308},
+}
 
 
 def decode_kernel_fingerprint() -> str:
@@ -49,6 +59,22 @@ def decode_kernel_fingerprint() -> str:
         with open(os.path.join(ROOT, "paper_2401_00588_amd", "csrc", name), "rb") as fh:
             h.update(fh.read())
     return h.hexdigest()[:16]
+
+
+def prefill_kernel_fingerprint() -> str:
+    import hashlib
+
+    h = hashlib.sha256()
+    for name in ("attn_prefill.hip", "vtc_internal.h"):
+        with open(os.path.join(ROOT, "paper_2401_00588_amd", "csrc", name), "rb") as fh:
+            h.update(fh.read())
+    return h.hexdigest()[:16]
+
+
+def decode_traffic(cfg):
+    """Measured HBM bytes per launch of the decode kernel on ``cfg``, or None (not measured, or the kernel changed)."""
+    table = DECODE_TRAFFIC_CFG3 if cfg == 3 else DECODE_TRAFFIC_OTHER.get(cfg, {})
+    return table.get(decode_kernel_fingerprint())
 
 
 def parse_args():
@@ -227,7 +253,8 @@ def decode_kernel_on(torch, vtc, cfg, steps=20, warmup=5):
     kv = batch.decode_kv_bytes
     return {"kernel": "decode_attend_kernel", "requests": batch.num_decode, "kv_bytes": kv, "dtype": sh.dtype,
             "kernel_avg_ms": round(avg, 5), "kernel_min_ms": round(ms[0], 5), "achieved": round(kv / avg / 1e6, 1),
-            "unit": "GB/s", "frac": round(kv / avg / 1e6 / HBM_PEAK_GBS, 4), "step_ms": round(step_ms, 5),
+            "unit": "GB/s", "frac": round(kv / avg / 1e6 / HBM_PEAK_GBS, 4), "traffic": decode_traffic(cfg),
+            "step_ms": round(step_ms, 5),
             "kv_cache_copies": n_copies}
 
 
@@ -282,7 +309,8 @@ def prefill_kernel_on_cfg5(torch, vtc, chunk, launches=24, reps=5, rotate=6):
     return {"kernel": "prefill_chunk_kernel", "chunk": chunk, "flops": batch.prefill_flops, "dtype": sh.dtype,
             "ms_per_launch": round(ms, 5), "ms_per_launch_min": round(per_launch[0], 5), "achieved": round(tf, 1),
             "unit": "TFLOP/s", "frac": round(tf / MFMA_PEAK_TFLOPS, 4),
-            "hbm_bytes": hbm_bytes, "hbm_gbs": round(hbm_bytes / ms / 1e6, 1),
+            "hbm_bytes": hbm_bytes, "traffic": PREFILL_TRAFFIC_CFG5[chunk].get(prefill_kernel_fingerprint()),
+            "hbm_gbs": round(hbm_bytes / ms / 1e6, 1),
             "hbm_frac": round(hbm_bytes / ms / 1e6 / HBM_PEAK_GBS, 4),
             "flop_per_byte": round(batch.prefill_flops / hbm_bytes, 1),
             "method": f"{launches} back-to-back launches over {rotate} distinct input sets per event pair"}
@@ -406,7 +434,7 @@ def main() -> int:
             "peak": HBM_PEAK_GBS,
             "unit": "GB/s",
             "frac": round(achieved / HBM_PEAK_GBS, 4),
-            "traffic": DECODE_TRAFFIC_CFG3.get(decode_kernel_fingerprint()) if cfg == 3 else None,
+            "traffic": decode_traffic(cfg),
             "kernel_avg_ms": round(kernel_avg_ms, 5),
             "kernel_min_ms": round(kernel_ms[0], 5),
             "kernel_median_ms": round(kernel_ms[len(kernel_ms) // 2], 5),
